@@ -1,0 +1,167 @@
+/*
+ * psd.h -- C ABI of the MI355X (gfx950) implementation of the per-layer gradient
+ * synchronisation compute of Poseidon's structure-aware communication protocol
+ * (arXiv 1512.06216, Section 4.3, Algorithm 3; issue order of Section 4.2, Algorithm 2).
+ *
+ * Symbols.  A fully-connected layer has M inputs and N outputs; W and Mom are N x M,
+ * row-major fp32 (one row per output neuron, Section 3.3).  B is the batch per worker
+ * (the paper's "batch size K"), P the number of workers, K = P*B the number of stacked
+ * samples.  U (K x N, errors) and V (K x M, activations) are the stacked sufficient
+ * factors of Section 4.3.1; row k = p*B + b holds sample b of worker p.
+ *
+ * Conventions for every entry point:
+ *   - returns a psd_status (0 = ok, negative = error); never throws, aborts or prints;
+ *   - pointers marked [dev] are device memory owned by the caller, never retained or
+ *     freed; pointers marked [host] are host memory read before the call returns;
+ *   - device work is enqueued on `stream` (a hipStream_t passed as void*, NULL = the
+ *     default stream) and the call returns without synchronising;
+ *   - [dev] base pointers must be 16-byte aligned, buffers must not overlap;
+ *   - sizes are validated on the host before anything is launched; no entry point
+ *     allocates device memory.
+ */
+#ifndef PSD_H
+#define PSD_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef int32_t psd_status;
+enum {
+    PSD_OK = 0,
+    PSD_E_INVALID = -1,     /* a size, enum value, alignment or leading dimension is out of range */
+    PSD_E_NULL = -2,        /* a required pointer is NULL */
+    PSD_E_UNSUPPORTED = -3, /* valid request this build cannot serve (e.g. route needs data not given) */
+    PSD_E_OVERFLOW = -4,    /* a communication volume does not fit in 64 bits */
+    PSD_E_HIP = -5          /* a HIP call failed; see psd_last_hip_error() */
+};
+
+enum { PSD_LAYER_CONV = 0, PSD_LAYER_FC = 1 };                      /* layer kind       */
+enum { PSD_ROUTE_PS_DENSE = 0, PSD_ROUTE_SFB = 1, PSD_ROUTE_SF_PS = 2 }; /* route        */
+enum { PSD_RULE_ALG3 = 0, PSD_RULE_SFB_VS_DENSE = 1 };              /* which comparison */
+enum { PSD_F32 = 0, PSD_BF16 = 1 };                                 /* factor dtype     */
+
+#define PSD_MAX_WORKERS 64  /* P, single-layer entry points */
+#define PSD_MAX_MULTI_SEGMENTS 16
+#define PSD_MAX_MULTI_WORKERS 16
+
+/* Result of the route selection of Algorithm 3. */
+typedef struct psd_plan {
+    int64_t M, N, B, P;
+    int32_t kind;            /* PSD_LAYER_* */
+    int32_t route_alg3;      /* Algorithm 3 as printed: conv -> PS_DENSE; FC -> SFB if
+                                cost_sfb <= cost_sf_ps, else SF_PS */
+    int32_t route_vs_dense;  /* the prose comparison of Section 4.3.1: FC -> SFB if
+                                cost_sfb <= cost_ps_dense, else PS_DENSE */
+    int32_t reserved;
+    uint64_t cost_sfb;       /* (P-1)^2 * B * (M+N) floats: factors to and from P-1 peers   */
+    uint64_t cost_ps_dense;  /* 2 * P * M * N floats: full matrices pushed and pulled       */
+    uint64_t cost_sf_ps;     /* P*B*(M+N) + P*M*N floats: factors up, full matrix back down */
+} psd_plan;
+
+/* Algorithm 3's route choice and the three communication volumes of Section 4.3.1.
+ * Host only, integer only.  M, N, B, P >= 1, P <= PSD_MAX_WORKERS.  For a conv layer M and
+ * N are any factorisation of its parameter count (only M*N matters).  `out` [host]. */
+psd_status psd_plan_layer(int32_t kind, int64_t M, int64_t N, int64_t B, int64_t P, psd_plan* out);
+
+/* Key range [*begin, *end) of shard s when keys 0..n-1 (the row-major flattened
+ * parameters of one layer) are split into S contiguous balanced ranges:
+ * begin = floor(s*n/S), end = floor((s+1)*n/S).  Needs 1 <= S <= n, 0 <= s < S.
+ * The paper's parameter server (Section 3.2) is sharded but does not define the ranges;
+ * this is the definition used throughout.  Host only. */
+psd_status psd_shard_range(int64_t n, int32_t S, int32_t s, int64_t* begin, int64_t* end);
+
+/* Leading dimension (in elements) that makes every row of a stacked factor matrix with
+ * `cols` columns start on a 16-byte boundary: cols rounded up to a multiple of 4 (f32)
+ * or 8 (bf16).  Returns 0 for bad arguments. */
+int64_t psd_factor_ld(int64_t cols, int32_t dtype);
+
+/* SFB steps 1-2 of Section 4.3.1 seen from the receiving worker: stack the P per-worker
+ * factor blocks into U and V, optionally rounding fp32 -> bf16 (nearest even; NaN stays a
+ * quiet NaN with its sign, +-Inf kept, overflow -> Inf).
+ *   delta_p [host] array of P [dev] pointers, each B x N fp32 row-major (errors)
+ *   act_p   [host] array of P [dev] pointers, each B x M fp32 row-major (activations)
+ *   U [dev] K x ldu, V [dev] K x ldv elements of `out_dtype`; U[p*B+b][j] = delta_p[p][b][j].
+ *   ldu >= N, ldv >= M, and ld * element size must be a multiple of 16 bytes; columns
+ *   N..ldu-1 (M..ldv-1) are written as zero.
+ * plan->M,N,B,P give the sizes. */
+psd_status psd_pack_factors(const psd_plan* plan, const float* const* delta_p,
+                            const float* const* act_p, int32_t out_dtype,
+                            void* U, int64_t ldu, void* V, int64_t ldv, void* stream);
+
+/* SFB step 3 and Algorithm 3's update line on one worker, fused:
+ *     dW[n][m] = sum_{k<K} U[k][n] * V[k][m]          (Eq. 5 summed over all P*B samples)
+ *     Mom <- mu*Mom + lr*dW ;  W <- W - Mom           (momentum SGD; sum over workers, no 1/P)
+ * U, V [dev] as written by psd_pack_factors (same dtype and leading dimensions);
+ * W, Mom [dev] N x M fp32 row-major, updated in place; dW is never stored.
+ * fp32 factors: fp32 MFMA, fp32 accumulation.  bf16 factors: bf16 MFMA with fp32
+ * accumulation; W and Mom stay fp32.  The same call serves the SF_PS route (the server
+ * runs the identical reconstruction over the same P*B factors). */
+psd_status psd_sync_fc_sfb(const psd_plan* plan, int32_t factor_dtype,
+                           const void* U, int64_t ldu, const void* V, int64_t ldv,
+                           float* W, float* Mom, float lr, float mu, void* stream);
+
+/* Parameter-server route (Algorithm 1 master node; Algorithm 3 non-FC branch): for every
+ * key i of every shard, g = sum_{p<P} G[p][i] (summed in p order, fp32), then the same
+ * momentum update on W[i], Mom[i].
+ *   G [host] array of P [dev] pointers to n fp32 each (read only); W, Mom [dev] n fp32,
+ *   in place.  1 <= P <= PSD_MAX_WORKERS; n >= 0 (n == 0 is a no-op); 1 <= S <= n.
+ * Shard s (psd_shard_range) is processed by the workgroups with blockIdx % S == s, which
+ * for S = 8 places one shard on each of the chip's 8 XCDs. */
+psd_status psd_sync_dense_ps(int64_t n, int32_t P, const float* const* G,
+                             float* W, float* Mom, float lr, float mu, int32_t S, void* stream);
+
+/* One segment (layer) of a batched parameter-server launch. */
+typedef struct psd_dense_segment {
+    int64_t n;                 /* keys in this layer */
+    int32_t P;                 /* copies, 1..PSD_MAX_MULTI_WORKERS */
+    int32_t S;                 /* shards, 1..n */
+    const float* const* G;     /* [host] array of P [dev] pointers */
+    float* W;                  /* [dev] n fp32 */
+    float* Mom;                /* [dev] n fp32 */
+} psd_dense_segment;
+
+/* Several layers' parameter-server updates in ONE kernel launch (the five small conv
+ * layers of an AlexNet-sized net would otherwise be launch-latency bound).
+ * 1 <= L <= PSD_MAX_MULTI_SEGMENTS; segs [host].  Same arithmetic as psd_sync_dense_ps. */
+psd_status psd_sync_dense_ps_multi(int32_t L, const psd_dense_segment* segs,
+                                   float lr, float mu, void* stream);
+
+/* One layer of an iteration for psd_sync_iteration. */
+typedef struct psd_layer_task {
+    psd_plan plan;             /* from psd_plan_layer */
+    int32_t factor_dtype;      /* FC: PSD_F32 or PSD_BF16 */
+    int32_t S;                 /* PS route: shards */
+    const float* const* delta_p; /* FC: [host] P [dev] pointers, B x N each */
+    const float* const* act_p;   /* FC: [host] P [dev] pointers, B x M each */
+    void* U; int64_t ldu;      /* FC: [dev] K x ldu stacked errors (written, then read) */
+    void* V; int64_t ldv;      /* FC: [dev] K x ldv stacked activations */
+    const float* const* G;     /* PS route: [host] P [dev] pointers, M*N fp32 each (may be
+                                  NULL for an FC layer that is routed to SFB / SF_PS) */
+    float* W; float* Mom;      /* [dev] N x M fp32 */
+    void* stream;              /* the stream this layer's work is enqueued on */
+} psd_layer_task;
+
+/* One iteration's synchronisation in the order of Algorithm 2: layers are given bottom-up
+ * (layers[0] is the lowest layer) and issued top-down, layer L-1 first, each on its own
+ * stream as if its gradient had just been produced by backpropagation.  Each layer follows
+ * the route its plan holds under `rule`: PS_DENSE -> psd_sync_dense_ps; SFB or SF_PS ->
+ * psd_pack_factors then psd_sync_fc_sfb.  Layers own disjoint parameters (Section 4.2), so
+ * no ordering between streams is needed; the caller synchronises the streams.
+ * Stops at and returns the first error. */
+psd_status psd_sync_iteration(int32_t L, const psd_layer_task* layers, float lr, float mu,
+                              int32_t rule);
+
+const char* psd_status_string(psd_status s);
+/* hipError_t value of the most recent failing HIP call on this thread (0 if none). */
+int32_t psd_last_hip_error(void);
+/* Library version, for the binding's load check. */
+int32_t psd_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* PSD_H */

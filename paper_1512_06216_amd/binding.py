@@ -1,0 +1,248 @@
+"""ctypes binding of libpsd.so (declared in include/psd.h): argument marshalling only.
+
+Every step of the path runs inside the library's HIP kernels; torch is used for device
+memory and streams.  There is no CPU fallback: if the library has not been built, the
+first call raises.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+
+import torch
+
+_PKG = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_PKG, "libpsd.so")
+
+OK, E_INVALID, E_NULL, E_UNSUPPORTED, E_OVERFLOW, E_HIP = 0, -1, -2, -3, -4, -5
+LAYER_CONV, LAYER_FC = 0, 1
+ROUTE_PS_DENSE, ROUTE_SFB, ROUTE_SF_PS = 0, 1, 2
+RULE_ALG3, RULE_SFB_VS_DENSE = 0, 1
+F32, BF16 = 0, 1
+ROUTE_NAMES = {ROUTE_PS_DENSE: "PS_DENSE", ROUTE_SFB: "SFB", ROUTE_SF_PS: "SF_PS"}
+MAX_WORKERS, MAX_MULTI_SEGMENTS, MAX_MULTI_WORKERS = 64, 16, 16
+
+_f32p = ctypes.POINTER(ctypes.c_float)
+_f32pp = ctypes.POINTER(_f32p)
+
+
+class Plan(ctypes.Structure):
+    _fields_ = [("M", ctypes.c_int64), ("N", ctypes.c_int64), ("B", ctypes.c_int64), ("P", ctypes.c_int64),
+                ("kind", ctypes.c_int32), ("route_alg3", ctypes.c_int32), ("route_vs_dense", ctypes.c_int32),
+                ("reserved", ctypes.c_int32), ("cost_sfb", ctypes.c_uint64), ("cost_ps_dense", ctypes.c_uint64),
+                ("cost_sf_ps", ctypes.c_uint64)]
+
+    def as_dict(self):
+        return {k: getattr(self, k) for k, _ in self._fields_ if k != "reserved"}
+
+    @property
+    def K(self):
+        return self.P * self.B
+
+
+class DenseSegment(ctypes.Structure):
+    _fields_ = [("n", ctypes.c_int64), ("P", ctypes.c_int32), ("S", ctypes.c_int32), ("G", _f32pp),
+                ("W", _f32p), ("Mom", _f32p)]
+
+
+class LayerTask(ctypes.Structure):
+    _fields_ = [("plan", Plan), ("factor_dtype", ctypes.c_int32), ("S", ctypes.c_int32),
+                ("delta_p", _f32pp), ("act_p", _f32pp),
+                ("U", ctypes.c_void_p), ("ldu", ctypes.c_int64), ("V", ctypes.c_void_p), ("ldv", ctypes.c_int64),
+                ("G", _f32pp), ("W", _f32p), ("Mom", _f32p), ("stream", ctypes.c_void_p)]
+
+
+class PsdError(RuntimeError):
+    def __init__(self, status, where):
+        self.status = status
+        msg = lib().psd_status_string(status).decode()
+        if status == E_HIP:
+            msg += " [hipError %d]" % lib().psd_last_hip_error()
+        super().__init__("%s: %s (status %d)" % (where, msg, status))
+
+
+# name -> (restype, argtypes); also the list of symbols the header declares
+SIGNATURES = {
+    "psd_plan_layer": (ctypes.c_int32, [ctypes.c_int32, ctypes.c_int64, ctypes.c_int64, ctypes.c_int64,
+                                        ctypes.c_int64, ctypes.POINTER(Plan)]),
+    "psd_shard_range": (ctypes.c_int32, [ctypes.c_int64, ctypes.c_int32, ctypes.c_int32,
+                                         ctypes.POINTER(ctypes.c_int64), ctypes.POINTER(ctypes.c_int64)]),
+    "psd_factor_ld": (ctypes.c_int64, [ctypes.c_int64, ctypes.c_int32]),
+    "psd_pack_factors": (ctypes.c_int32, [ctypes.POINTER(Plan), _f32pp, _f32pp, ctypes.c_int32, ctypes.c_void_p,
+                                          ctypes.c_int64, ctypes.c_void_p, ctypes.c_int64, ctypes.c_void_p]),
+    "psd_sync_fc_sfb": (ctypes.c_int32, [ctypes.POINTER(Plan), ctypes.c_int32, ctypes.c_void_p, ctypes.c_int64,
+                                         ctypes.c_void_p, ctypes.c_int64, ctypes.c_void_p, ctypes.c_void_p,
+                                         ctypes.c_float, ctypes.c_float, ctypes.c_void_p]),
+    "psd_sync_dense_ps": (ctypes.c_int32, [ctypes.c_int64, ctypes.c_int32, _f32pp, ctypes.c_void_p, ctypes.c_void_p,
+                                           ctypes.c_float, ctypes.c_float, ctypes.c_int32, ctypes.c_void_p]),
+    "psd_sync_dense_ps_multi": (ctypes.c_int32, [ctypes.c_int32, ctypes.POINTER(DenseSegment), ctypes.c_float,
+                                                 ctypes.c_float, ctypes.c_void_p]),
+    "psd_sync_iteration": (ctypes.c_int32, [ctypes.c_int32, ctypes.POINTER(LayerTask), ctypes.c_float,
+                                            ctypes.c_float, ctypes.c_int32]),
+    "psd_status_string": (ctypes.c_char_p, [ctypes.c_int32]),
+    "psd_last_hip_error": (ctypes.c_int32, []),
+    "psd_version": (ctypes.c_int32, []),
+}
+
+_lib = None
+
+
+def lib():
+    """Loads libpsd.so; raises if it is missing (build it with __graft_entry__.build())."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise RuntimeError("libpsd.so is not built (%s): run `python -c 'import __graft_entry__ as g; "
+                               "g.build()'`; there is no fallback path" % LIB_PATH)
+        L = ctypes.CDLL(LIB_PATH)
+        for name, (res, args) in SIGNATURES.items():
+            fn = getattr(L, name)
+            fn.restype, fn.argtypes = res, args
+        _lib = L
+    return _lib
+
+
+def _check(status, where):
+    if status != OK:
+        raise PsdError(status, where)
+
+
+def _stream_handle(stream):
+    if stream is None:
+        return ctypes.c_void_p(torch.cuda.current_stream().cuda_stream)
+    if isinstance(stream, int):
+        return ctypes.c_void_p(stream)
+    return ctypes.c_void_p(stream.cuda_stream)
+
+
+def _dev_ptr(t, dtype, min_elems, what):
+    """Device pointer of a tensor after checking it can hold what the kernel will touch."""
+    if not (isinstance(t, torch.Tensor) and t.is_cuda and t.is_contiguous()):
+        raise ValueError("%s must be a contiguous CUDA tensor" % what)
+    if t.dtype not in (dtype if isinstance(dtype, tuple) else (dtype,)):
+        raise ValueError("%s has dtype %s" % (what, t.dtype))
+    if t.numel() < min_elems:
+        raise ValueError("%s holds %d elements, needs %d" % (what, t.numel(), min_elems))
+    return t.data_ptr()
+
+
+def _ptr_array(tensors, min_elems, what):
+    arr = (_f32p * len(tensors))()
+    for i, t in enumerate(tensors):
+        arr[i] = ctypes.cast(_dev_ptr(t, torch.float32, min_elems, "%s[%d]" % (what, i)), _f32p)
+    return arr
+
+
+_FACTOR_TORCH = {F32: (torch.float32,), BF16: (torch.bfloat16, torch.int16, torch.uint16)}
+
+
+# ---------------------------------------------------------------------------------------
+def plan_layer(kind, M, N, B, P):
+    p = Plan()
+    _check(lib().psd_plan_layer(kind, M, N, B, P, ctypes.byref(p)), "psd_plan_layer")
+    return p
+
+
+def shard_range(n, S, s):
+    b, e = ctypes.c_int64(), ctypes.c_int64()
+    _check(lib().psd_shard_range(n, S, s, ctypes.byref(b), ctypes.byref(e)), "psd_shard_range")
+    return b.value, e.value
+
+
+def factor_ld(cols, dtype):
+    ld = lib().psd_factor_ld(cols, dtype)
+    if ld <= 0:
+        raise PsdError(E_INVALID, "psd_factor_ld")
+    return ld
+
+
+def alloc_factors(plan, dtype, device="cuda"):
+    """Device buffers for the stacked factors: (U, ldu, V, ldv).  Memory only."""
+    ldu, ldv = factor_ld(plan.N, dtype), factor_ld(plan.M, dtype)
+    td = torch.float32 if dtype == F32 else torch.bfloat16
+    U = torch.empty((plan.K, ldu), dtype=td, device=device)
+    V = torch.empty((plan.K, ldv), dtype=td, device=device)
+    return U, ldu, V, ldv
+
+
+def pack_factors(plan, delta, act, out_dtype, U, ldu, V, ldv, stream=None):
+    if len(delta) != plan.P or len(act) != plan.P:
+        raise ValueError("need P per-worker blocks")
+    d = _ptr_array(delta, plan.B * plan.N, "delta")
+    a = _ptr_array(act, plan.B * plan.M, "act")
+    up = _dev_ptr(U, _FACTOR_TORCH.get(out_dtype, ()), plan.K * ldu, "U")
+    vp = _dev_ptr(V, _FACTOR_TORCH.get(out_dtype, ()), plan.K * ldv, "V")
+    _check(lib().psd_pack_factors(ctypes.byref(plan), d, a, out_dtype, up, ldu, vp, ldv, _stream_handle(stream)),
+           "psd_pack_factors")
+
+
+def sync_fc_sfb(plan, factor_dtype, U, ldu, V, ldv, W, Mom, lr, mu, stream=None):
+    up = _dev_ptr(U, _FACTOR_TORCH.get(factor_dtype, ()), plan.K * ldu, "U")
+    vp = _dev_ptr(V, _FACTOR_TORCH.get(factor_dtype, ()), plan.K * ldv, "V")
+    wp = _dev_ptr(W, torch.float32, plan.N * plan.M, "W")
+    mp = _dev_ptr(Mom, torch.float32, plan.N * plan.M, "Mom")
+    _check(lib().psd_sync_fc_sfb(ctypes.byref(plan), factor_dtype, up, ldu, vp, ldv, wp, mp, lr, mu,
+                                 _stream_handle(stream)), "psd_sync_fc_sfb")
+
+
+def sync_dense_ps(G, W, Mom, lr, mu, S, stream=None):
+    n = W.numel()
+    g = _ptr_array(G, n, "G")
+    wp = _dev_ptr(W, torch.float32, n, "W")
+    mp = _dev_ptr(Mom, torch.float32, n, "Mom")
+    _check(lib().psd_sync_dense_ps(n, len(G), g, wp, mp, lr, mu, S, _stream_handle(stream)), "psd_sync_dense_ps")
+
+
+def sync_dense_ps_multi(layers, lr, mu, stream=None):
+    """layers: list of (G_list, W, Mom, S)."""
+    segs = (DenseSegment * len(layers))()
+    keep = []
+    for i, (G, W, Mom, S) in enumerate(layers):
+        n = W.numel()
+        g = _ptr_array(G, n, "G")
+        keep.append(g)
+        segs[i].n, segs[i].P, segs[i].S = n, len(G), S
+        segs[i].G = ctypes.cast(g, _f32pp)
+        segs[i].W = ctypes.cast(_dev_ptr(W, torch.float32, n, "W"), _f32p)
+        segs[i].Mom = ctypes.cast(_dev_ptr(Mom, torch.float32, n, "Mom"), _f32p)
+    _check(lib().psd_sync_dense_ps_multi(len(layers), segs, lr, mu, _stream_handle(stream)),
+           "psd_sync_dense_ps_multi")
+
+
+class Iteration:
+    """Marshalled, reusable argument block for psd_sync_iteration (layers bottom-up).
+
+    Each layer is a dict: FC  -> plan, factor_dtype, delta, act, U, ldu, V, ldv, W, Mom, stream
+                         conv -> plan, G, S, W, Mom, stream
+    Building it does no device work; run() makes the single library call.
+    """
+
+    def __init__(self, layers):
+        self.tasks = (LayerTask * len(layers))()
+        self._keep = []
+        for i, L in enumerate(layers):
+            t = self.tasks[i]
+            plan = L["plan"]
+            t.plan = plan
+            n = plan.M * plan.N
+            t.W = ctypes.cast(_dev_ptr(L["W"], torch.float32, n, "W"), _f32p)
+            t.Mom = ctypes.cast(_dev_ptr(L["Mom"], torch.float32, n, "Mom"), _f32p)
+            t.stream = _stream_handle(L.get("stream"))
+            t.S = L.get("S", 1)
+            t.factor_dtype = L.get("factor_dtype", F32)
+            if L.get("G") is not None:
+                g = _ptr_array(L["G"], n, "G")
+                self._keep.append(g)
+                t.G = ctypes.cast(g, _f32pp)
+            if L.get("delta") is not None:
+                d = _ptr_array(L["delta"], plan.B * plan.N, "delta")
+                a = _ptr_array(L["act"], plan.B * plan.M, "act")
+                self._keep += [d, a]
+                t.delta_p, t.act_p = ctypes.cast(d, _f32pp), ctypes.cast(a, _f32pp)
+                fd = _FACTOR_TORCH.get(t.factor_dtype, ())
+                t.U, t.ldu = _dev_ptr(L["U"], fd, plan.K * L["ldu"], "U"), L["ldu"]
+                t.V, t.ldv = _dev_ptr(L["V"], fd, plan.K * L["ldv"], "V"), L["ldv"]
+        self.L = len(layers)
+
+    def run(self, lr, mu, rule=RULE_ALG3):
+        _check(lib().psd_sync_iteration(self.L, self.tasks, lr, mu, rule), "psd_sync_iteration")

@@ -1,0 +1,168 @@
+// Parameter-server route on one GPU: per key, sum the P dense gradient copies and apply
+// the momentum-SGD update (Algorithm 1 master node; Algorithm 3 non-FC branch).
+//
+// HBM-bound streaming kernel: (4P + 16) bytes per key, P + 3 flops.  The reduction runs
+// over the P copies, which all sit in one lane's registers, so there is nothing to reduce
+// across lanes and nothing to stage in LDS: the design is all about keeping many 16-byte
+// loads in flight per lane and every wavefront access a full 1 KiB contiguous segment.
+//
+// Grid: workgroup g serves shard g % S, chunk g / S of that shard.  Hardware dispatches
+// consecutive workgroups round-robin over the 8 XCDs, so with S = 8 each key-range shard
+// is streamed by exactly one XCD (one L2), like one server process per shard.
+#include "psd_internal.h"
+
+namespace psd {
+
+constexpr int kDenseThreads = 256;
+constexpr int kDenseUnroll = 2;                                   // float4 per lane per chunk
+constexpr int64_t kDenseChunk = int64_t(kDenseThreads) * 4 * kDenseUnroll;  // keys per workgroup
+
+int32_t dense_chunks_for(int64_t n, int32_t S)
+{
+    const int64_t longest = (n + S - 1) / S;   // floor((s+1)n/S) - floor(sn/S) <= ceil(n/S)
+    return static_cast<int32_t>((longest + kDenseChunk - 1) / kDenseChunk);
+}
+
+namespace {
+
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+
+// 16-byte streaming load: the gradient copies are read exactly once
+__device__ __forceinline__ float4 ld_stream(const float* p)
+{
+    const f32x4 v = __builtin_nontemporal_load(reinterpret_cast<const f32x4*>(p));
+    return make_float4(v.x, v.y, v.z, v.w);
+}
+
+__device__ __forceinline__ void update1(float g, float& w, float& mom, float lr, float mu)
+{
+    mom = __fmaf_rn(mu, mom, lr * g);
+    w = w - mom;
+}
+
+// keys [lo, hi) of one layer; PC > 0: number of copies known at compile time
+template <int PC>
+__device__ __forceinline__ void dense_span(const float* const* __restrict__ G, int P, float* __restrict__ W,
+                                           float* __restrict__ Mom, int64_t lo, int64_t hi, float lr, float mu)
+{
+    const int nP = PC > 0 ? PC : P;
+    // W, Mom and every G[p] are 16-byte aligned, so key i is float4-aligned iff i % 4 == 0
+    int64_t lo4 = (lo + 3) & ~int64_t(3);
+    if (lo4 > hi) lo4 = hi;
+    const int64_t hi4 = lo4 + ((hi - lo4) & ~int64_t(3));
+
+    int64_t idx[kDenseUnroll];
+    float4 acc[kDenseUnroll], w[kDenseUnroll], m[kDenseUnroll];
+#pragma unroll
+    for (int u = 0; u < kDenseUnroll; ++u) {
+        idx[u] = lo4 + (int64_t(u) * kDenseThreads + threadIdx.x) * 4;
+        if (idx[u] < hi4) {
+            if constexpr (PC > 0) {
+                float4 g[PC];
+#pragma unroll
+                for (int p = 0; p < PC; ++p) g[p] = ld_stream(G[p] + idx[u]);
+                w[u] = *reinterpret_cast<const float4*>(W + idx[u]);
+                m[u] = *reinterpret_cast<const float4*>(Mom + idx[u]);
+                acc[u] = g[0];
+#pragma unroll
+                for (int p = 1; p < PC; ++p) {
+                    acc[u].x += g[p].x; acc[u].y += g[p].y; acc[u].z += g[p].z; acc[u].w += g[p].w;
+                }
+            } else {
+                w[u] = *reinterpret_cast<const float4*>(W + idx[u]);
+                m[u] = *reinterpret_cast<const float4*>(Mom + idx[u]);
+                acc[u] = ld_stream(G[0] + idx[u]);
+                for (int p = 1; p < nP; ++p) {
+                    const float4 g = ld_stream(G[p] + idx[u]);
+                    acc[u].x += g.x; acc[u].y += g.y; acc[u].z += g.z; acc[u].w += g.w;
+                }
+            }
+        }
+    }
+#pragma unroll
+    for (int u = 0; u < kDenseUnroll; ++u) {
+        if (idx[u] < hi4) {
+            update1(acc[u].x, w[u].x, m[u].x, lr, mu);
+            update1(acc[u].y, w[u].y, m[u].y, lr, mu);
+            update1(acc[u].z, w[u].z, m[u].z, lr, mu);
+            update1(acc[u].w, w[u].w, m[u].w, lr, mu);
+            *reinterpret_cast<float4*>(Mom + idx[u]) = m[u];
+            *reinterpret_cast<float4*>(W + idx[u]) = w[u];
+        }
+    }
+    // at most 3 unaligned keys at each end of the span
+    const int nh = static_cast<int>(lo4 - lo), nt = static_cast<int>(hi - hi4);
+    const int t = threadIdx.x;
+    if (t < nh + nt) {
+        const int64_t i = t < nh ? lo + t : hi4 + (t - nh);
+        float g = G[0][i];
+        for (int p = 1; p < nP; ++p) g += G[p][i];
+        float wv = W[i], mv = Mom[i];
+        update1(g, wv, mv, lr, mu);
+        Mom[i] = mv;
+        W[i] = wv;
+    }
+}
+
+__device__ __forceinline__ void dense_block(const float* const* G, int P, float* W, float* Mom, int64_t n, int S,
+                                            int local_block, float lr, float mu)
+{
+    const int s = local_block % S;
+    const int64_t c = local_block / S;
+    // shard s owns [floor(s n / S), floor((s+1) n / S)); n < 2^40 and S <= n keep this in 64 bits
+    // when S < 2^23; larger S take the 128-bit path
+    int64_t begin, end;
+    if (S < (1 << 23)) {
+        begin = (int64_t(s) * n) / S;
+        end = (int64_t(s + 1) * n) / S;
+    } else {
+        begin = static_cast<int64_t>((static_cast<__int128>(s) * n) / S);
+        end = static_cast<int64_t>((static_cast<__int128>(s + 1) * n) / S);
+    }
+    const int64_t lo = begin + c * kDenseChunk;
+    if (lo >= end) return;
+    const int64_t hi = lo + kDenseChunk < end ? lo + kDenseChunk : end;
+    switch (P) {
+        case 8: dense_span<8>(G, P, W, Mom, lo, hi, lr, mu); break;
+        case 4: dense_span<4>(G, P, W, Mom, lo, hi, lr, mu); break;
+        case 2: dense_span<2>(G, P, W, Mom, lo, hi, lr, mu); break;
+        case 16: dense_span<16>(G, P, W, Mom, lo, hi, lr, mu); break;
+        default: dense_span<0>(G, P, W, Mom, lo, hi, lr, mu); break;
+    }
+}
+
+__global__ void __launch_bounds__(kDenseThreads) dense_ps_table_kernel(const DenseTable t, float lr, float mu)
+{
+    // which layer does this workgroup belong to (at most 16 segments: linear scan)
+    int l = 0;
+    const int b = blockIdx.x;
+    for (int j = 1; j < t.L; ++j)
+        if (b >= t.seg[j].block_begin) l = j;
+    const DenseSeg& sg = t.seg[l];
+    dense_block(sg.G, sg.P, sg.W, sg.Mom, sg.n, sg.S, b - sg.block_begin, lr, mu);
+}
+
+__global__ void __launch_bounds__(kDenseThreads) dense_ps_wide_kernel(const DenseWide a, float lr, float mu)
+{
+    dense_block(a.G, a.P, a.W, a.Mom, a.n, a.S, blockIdx.x, lr, mu);
+}
+
+}  // namespace
+
+psd_status launch_dense_table(const DenseTable& t, int32_t total_blocks, float lr, float mu, hipStream_t st)
+{
+    hipLaunchKernelGGL(dense_ps_table_kernel, dim3(total_blocks), dim3(kDenseThreads), 0, st, t, lr, mu);
+    PSD_HIP_TRY(hipGetLastError());
+    return PSD_OK;
+}
+
+psd_status launch_dense_wide(const DenseWide& a, float lr, float mu, hipStream_t st)
+{
+    const int64_t blocks = int64_t(a.chunks) * a.S;
+    if (blocks < 1 || blocks > (int64_t(1) << 30)) return PSD_E_INVALID;
+    hipLaunchKernelGGL(dense_ps_wide_kernel, dim3(static_cast<uint32_t>(blocks)), dim3(kDenseThreads), 0, st, a, lr, mu);
+    PSD_HIP_TRY(hipGetLastError());
+    return PSD_OK;
+}
+
+}  // namespace psd

@@ -1,0 +1,160 @@
+"""Host-only checks of the C-ABI library: it loads, exports what include/psd.h declares,
+its integer logic equals the oracle bit for bit, and bad arguments come back as status
+codes before anything is launched (no GPU needed)."""
+import ctypes
+import itertools
+import os
+import re
+
+import pytest
+
+from oracle import psd_oracle as orc
+from paper_1512_06216_amd import binding as psd
+from tests.conftest import ROOT
+
+
+def test_library_exports_every_declared_symbol():
+    text = open(os.path.join(ROOT, "include", "psd.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    declared = set(re.findall(r"\b(psd_[a-z0-9_]+)\s*\(", text))
+    assert declared == set(psd.SIGNATURES), declared ^ set(psd.SIGNATURES)
+    L = psd.lib()
+    for name in declared:
+        assert getattr(L, name) is not None
+    assert L.psd_version() == 1
+
+
+def test_struct_layouts_match_the_header():
+    assert ctypes.sizeof(psd.Plan) == 4 * 8 + 4 * 4 + 3 * 8
+    assert ctypes.sizeof(psd.DenseSegment) == 8 + 4 + 4 + 3 * 8
+    assert ctypes.sizeof(psd.LayerTask) == ctypes.sizeof(psd.Plan) + 8 + 2 * 8 + 4 * 8 + 8 + 2 * 8 + 8
+
+
+GRID = list(itertools.product([1, 3, 128, 256, 1000, 4096, 9216], [1, 2, 128, 1000, 4096, 21841],
+                              [1, 32, 64, 128, 256, 4000], [1, 2, 3, 4, 8, 16, 33, 64]))
+
+
+def test_plan_equals_oracle_on_a_grid():
+    for kind in (psd.LAYER_FC, psd.LAYER_CONV):
+        for M, N, B, P in GRID:
+            got = psd.plan_layer(kind, M, N, B, P).as_dict()
+            want = orc.plan_layer(kind, M, N, B, P)
+            assert got == want, (kind, M, N, B, P)
+
+
+def test_plan_paper_example_and_config2_discrepancy():
+    p = psd.plan_layer(psd.LAYER_FC, 4096, 4096, 256, 4)
+    assert (p.cost_sfb, p.cost_ps_dense, p.cost_sf_ps) == (18874368, 134217728, 75497472)
+    # 4096 -> 1000 at B=256, P=8: Algorithm 3 as printed sends factors to the server,
+    # the SFB-vs-full-matrix comparison of the prose picks SFB
+    p = psd.plan_layer(psd.LAYER_FC, 4096, 1000, 256, 8)
+    assert p.route_alg3 == psd.ROUTE_SF_PS and p.route_vs_dense == psd.ROUTE_SFB
+
+
+def test_plan_errors():
+    L = psd.lib()
+    out = psd.Plan()
+    assert L.psd_plan_layer(psd.LAYER_FC, 4, 4, 4, 4, None) == psd.E_NULL
+    for args in [(2, 4, 4, 4, 4), (1, 0, 4, 4, 4), (1, 4, -1, 4, 4), (1, 4, 4, 0, 4), (1, 4, 4, 4, 0), (1, 4, 4, 4, 65)]:
+        assert L.psd_plan_layer(*args, ctypes.byref(out)) == psd.E_INVALID
+    assert L.psd_plan_layer(1, 2 ** 31, 2 ** 31, 1, 4, ctypes.byref(out)) == psd.E_OVERFLOW
+    assert L.psd_plan_layer(1, 2 ** 62, 2 ** 62, 1, 2, ctypes.byref(out)) == psd.E_OVERFLOW
+    with pytest.raises(OverflowError):
+        orc.plan_layer(1, 2 ** 31, 2 ** 31, 1, 4)
+    # largest cost just fits
+    p = psd.plan_layer(1, 2 ** 30, 2 ** 30, 1, 4).as_dict()
+    assert p == orc.plan_layer(1, 2 ** 30, 2 ** 30, 1, 4)
+    assert b"overflow" in L.psd_status_string(psd.E_OVERFLOW)
+
+
+def test_shard_range_equals_oracle():
+    for n in list(range(1, 30)) + [97, 34848, 307200, 884736, 21841 * 4096, 2 ** 40 - 1]:
+        for S in [1, 2, 3, 7, 8, 16, 29]:
+            if S > n:
+                continue
+            for s in {0, S // 2, S - 1}:
+                assert psd.shard_range(n, S, s) == orc.shard_range(n, S, s)
+    L = psd.lib()
+    b, e = ctypes.c_int64(), ctypes.c_int64()
+    for n, S, s in [(4, 5, 0), (4, 0, 0), (4, 2, 2), (4, 2, -1), (0, 1, 0)]:
+        assert L.psd_shard_range(n, S, s, ctypes.byref(b), ctypes.byref(e)) == psd.E_INVALID
+    assert L.psd_shard_range(4, 2, 0, None, ctypes.byref(e)) == psd.E_NULL
+
+
+def test_factor_ld():
+    assert psd.factor_ld(1000, psd.F32) == 1000 and psd.factor_ld(1001, psd.F32) == 1004
+    assert psd.factor_ld(21841, psd.BF16) == 21848 and psd.factor_ld(4096, psd.BF16) == 4096
+    assert psd.lib().psd_factor_ld(0, psd.F32) == 0 and psd.lib().psd_factor_ld(8, 7) == 0
+
+
+def _fake(addr):
+    return ctypes.c_void_p(addr)
+
+
+def test_device_entry_points_reject_bad_arguments_before_launching():
+    L = psd.lib()
+    plan = psd.plan_layer(psd.LAYER_FC, 8, 8, 2, 2)
+    f32p = ctypes.POINTER(ctypes.c_float)
+    good = (f32p * 2)(ctypes.cast(0x1000, f32p), ctypes.cast(0x2000, f32p))
+    odd = (f32p * 2)(ctypes.cast(0x1004, f32p), ctypes.cast(0x2000, f32p))
+    null = (f32p * 2)(ctypes.cast(0x1000, f32p), None)
+    U, V, W, Mom = _fake(0x10000), _fake(0x20000), _fake(0x30000), _fake(0x40000)
+    pp = ctypes.byref(plan)
+    # pack
+    assert L.psd_pack_factors(None, good, good, psd.F32, U, 8, V, 8, None) == psd.E_NULL
+    assert L.psd_pack_factors(pp, good, good, psd.F32, None, 8, V, 8, None) == psd.E_NULL
+    assert L.psd_pack_factors(pp, null, good, psd.F32, U, 8, V, 8, None) == psd.E_NULL
+    assert L.psd_pack_factors(pp, odd, good, psd.F32, U, 8, V, 8, None) == psd.E_INVALID
+    assert L.psd_pack_factors(pp, good, good, 5, U, 8, V, 8, None) == psd.E_INVALID
+    assert L.psd_pack_factors(pp, good, good, psd.F32, U, 4, V, 8, None) == psd.E_INVALID      # ld < N
+    assert L.psd_pack_factors(pp, good, good, psd.F32, U, 9, V, 8, None) == psd.E_INVALID      # ld*4 % 16
+    assert L.psd_pack_factors(pp, good, good, psd.BF16, U, 12, V, 8, None) == psd.E_INVALID    # ld*2 % 16
+    assert L.psd_pack_factors(pp, good, good, psd.F32, _fake(0x10004), 8, V, 8, None) == psd.E_INVALID
+    # sfb
+    assert L.psd_sync_fc_sfb(pp, psd.F32, U, 8, V, 8, None, Mom, 0.1, 0.9, None) == psd.E_NULL
+    assert L.psd_sync_fc_sfb(pp, 9, U, 8, V, 8, W, Mom, 0.1, 0.9, None) == psd.E_INVALID
+    assert L.psd_sync_fc_sfb(pp, psd.F32, U, 8, V, 8, W, W, 0.1, 0.9, None) == psd.E_INVALID
+    assert L.psd_sync_fc_sfb(pp, psd.F32, U, 8, V, 8, _fake(0x30008), Mom, 0.1, 0.9, None) == psd.E_INVALID
+    assert L.psd_sync_fc_sfb(pp, psd.BF16, U, 8, V, 7, W, Mom, 0.1, 0.9, None) == psd.E_INVALID
+    bad = psd.Plan()
+    ctypes.memmove(ctypes.byref(bad), ctypes.byref(plan), ctypes.sizeof(plan))
+    bad.P = 0
+    assert L.psd_sync_fc_sfb(ctypes.byref(bad), psd.F32, U, 8, V, 8, W, Mom, 0.1, 0.9, None) == psd.E_INVALID
+    # dense
+    assert L.psd_sync_dense_ps(16, 2, None, W, Mom, 0.1, 0.9, 1, None) == psd.E_NULL
+    assert L.psd_sync_dense_ps(16, 2, null, W, Mom, 0.1, 0.9, 1, None) == psd.E_NULL
+    assert L.psd_sync_dense_ps(16, 0, good, W, Mom, 0.1, 0.9, 1, None) == psd.E_INVALID
+    assert L.psd_sync_dense_ps(16, 65, good, W, Mom, 0.1, 0.9, 1, None) == psd.E_INVALID
+    assert L.psd_sync_dense_ps(16, 2, good, W, Mom, 0.1, 0.9, 17, None) == psd.E_INVALID     # S > n
+    assert L.psd_sync_dense_ps(16, 2, good, W, Mom, 0.1, 0.9, 0, None) == psd.E_INVALID
+    assert L.psd_sync_dense_ps(-1, 2, good, W, Mom, 0.1, 0.9, 1, None) == psd.E_INVALID
+    assert L.psd_sync_dense_ps(16, 2, odd, W, Mom, 0.1, 0.9, 1, None) == psd.E_INVALID
+    assert L.psd_sync_dense_ps(0, 2, good, W, Mom, 0.1, 0.9, 1, None) == psd.OK              # empty layer: no-op
+    # multi
+    seg = (psd.DenseSegment * 1)()
+    seg[0].n, seg[0].P, seg[0].S = 16, 2, 1
+    seg[0].G = ctypes.cast(good, ctypes.POINTER(f32p))
+    seg[0].W, seg[0].Mom = ctypes.cast(0x30000, f32p), ctypes.cast(0x40000, f32p)
+    assert L.psd_sync_dense_ps_multi(0, seg, 0.1, 0.9, None) == psd.E_INVALID
+    assert L.psd_sync_dense_ps_multi(17, seg, 0.1, 0.9, None) == psd.E_INVALID
+    assert L.psd_sync_dense_ps_multi(1, None, 0.1, 0.9, None) == psd.E_NULL
+    seg[0].P = 17
+    assert L.psd_sync_dense_ps_multi(1, seg, 0.1, 0.9, None) == psd.E_INVALID
+    seg[0].P, seg[0].n = 2, 0
+    assert L.psd_sync_dense_ps_multi(1, seg, 0.1, 0.9, None) == psd.OK                       # nothing to do
+    # iteration
+    assert L.psd_sync_iteration(1, None, 0.1, 0.9, 0) == psd.E_NULL
+    task = (psd.LayerTask * 1)()
+    task[0].plan = psd.plan_layer(psd.LAYER_CONV, 8, 8, 2, 2)
+    assert L.psd_sync_iteration(0, task, 0.1, 0.9, 0) == psd.E_INVALID
+    assert L.psd_sync_iteration(1, task, 0.1, 0.9, 7) == psd.E_INVALID
+    assert L.psd_sync_iteration(1, task, 0.1, 0.9, 0) == psd.E_UNSUPPORTED                   # PS route without G
+    for s in (0, -1, -2, -3, -4, -5, -99):
+        assert L.psd_status_string(s)
+
+
+def test_binding_fails_loudly_without_the_library(monkeypatch):
+    monkeypatch.setattr(psd, "_lib", None)
+    monkeypatch.setattr(psd, "LIB_PATH", "/nonexistent/libpsd.so")
+    with pytest.raises(RuntimeError, match="not built"):
+        psd.plan_layer(psd.LAYER_FC, 4, 4, 4, 4)

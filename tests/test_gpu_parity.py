@@ -1,0 +1,329 @@
+"""Parity of the HIP path (through the C ABI) with the CPU oracle, element by element.
+
+Bars: bit-exact for packing, shard indexing, route decisions and for integer-valued
+inputs (every partial sum below 2^24, so fp32 results do not depend on summation order);
+relative Frobenius error <= 1e-5 for fp32 factors and for bf16 factors against the oracle
+fed the same rounded factors; <= 2e-2 for bf16 factors against the oracle fed the
+unrounded fp32 factors.  Errors are taken on three tensors: Mom', W' - W, and W'.
+"""
+import numpy as np
+import pytest
+import torch
+
+from oracle import psd_oracle as orc
+from paper_1512_06216_amd import binding as psd
+from paper_1512_06216_amd import inputs
+
+pytestmark = pytest.mark.gpu
+
+TOL_F32 = 1e-5
+TOL_BF16_VS_F32 = 2e-2
+DEV = "cuda:0"
+
+
+def dev(a):
+    return torch.from_numpy(np.ascontiguousarray(a)).to(DEV)
+
+
+def bits16(t):
+    return t.view(torch.int16).cpu().numpy().view(np.uint16)
+
+
+def three_errors(W0, W_gpu, Mom_gpu, W_ref, Mom_ref):
+    W0 = W0.astype(np.float64)
+    return (orc.rel_frob(Mom_gpu, Mom_ref),
+            orc.rel_frob(W_gpu.astype(np.float64) - W0, W_ref.astype(np.float64) - W0),
+            orc.rel_frob(W_gpu, W_ref))
+
+
+def run_pack(d, dtype):
+    plan = psd.plan_layer(psd.LAYER_FC, d["M"], d["N"], d["B"], d["P"])
+    U, ldu, V, ldv = psd.alloc_factors(plan, dtype, DEV)
+    # poison so that unwritten elements show
+    U.view(torch.int16).fill_(0x7fc1)
+    V.view(torch.int16).fill_(0x7fc1)
+    delta = [dev(x) for x in d["delta"]]
+    act = [dev(x) for x in d["act"]]
+    psd.pack_factors(plan, delta, act, dtype, U, ldu, V, ldv)
+    torch.cuda.synchronize()
+    return plan, U, ldu, V, ldv
+
+
+def run_sfb(d, dtype, lr, mu):
+    plan, U, ldu, V, ldv = run_pack(d, dtype)
+    W, Mom = dev(d["W"]), dev(d["Mom"])
+    psd.sync_fc_sfb(plan, dtype, U, ldu, V, ldv, W, Mom, lr, mu)
+    torch.cuda.synchronize()
+    return W.cpu().numpy(), Mom.cpu().numpy(), (U, V)
+
+
+# ---------------------------------------------------------------------------------------
+# pack / stack: bit-exact
+# ---------------------------------------------------------------------------------------
+@pytest.mark.parametrize("M,N,B,P", [(256, 128, 32, 4), (37, 29, 3, 5), (1, 1, 1, 1), (1001, 2185, 7, 3),
+                                     (8, 21841, 2, 2), (4096, 1000, 16, 8)])
+@pytest.mark.parametrize("dtype", [psd.F32, psd.BF16])
+def test_pack_bit_exact(M, N, B, P, dtype):
+    d = inputs.fc_layer(M, N, B, P, seed=100 + M % 7)
+    # make a few values special so that rounding corner cases travel through the kernel
+    d["delta"][0].flat[0] = np.float32(1.0 + 2.0 ** -8)       # bf16 tie
+    d["act"][P - 1].flat[-1] = np.float32(np.inf)
+    d["act"][0].flat[0] = np.float32(1e-40)                    # subnormal
+    plan, U, ldu, V, ldv = run_pack(d, dtype)
+    name = "f32" if dtype == psd.F32 else "bf16"
+    Uo, Vo = orc.pack_factors(d["delta"], d["act"], name)
+    if dtype == psd.F32:
+        Ug, Vg = U.cpu().numpy().view(np.uint32), V.cpu().numpy().view(np.uint32)
+        Uo, Vo = Uo.view(np.uint32), Vo.view(np.uint32)
+    else:
+        Ug, Vg = bits16(U), bits16(V)
+    assert np.array_equal(Ug[:, :N], Uo) and np.array_equal(Vg[:, :M], Vo)
+    assert not Ug[:, N:].any() and not Vg[:, M:].any()          # padding columns are zero
+
+
+def test_pack_nan_stays_nan():
+    d = inputs.fc_layer(16, 8, 2, 2, seed=3)
+    d["delta"][1][1, 3] = np.float32(np.nan)
+    plan, U, ldu, V, ldv = run_pack(d, psd.BF16)
+    Uo, _ = orc.pack_factors(d["delta"], d["act"], "bf16")
+    assert np.array_equal(bits16(U)[:, :8], Uo)
+
+
+# ---------------------------------------------------------------------------------------
+# dense parameter-server route
+# ---------------------------------------------------------------------------------------
+DENSE_CASES = [(1, 1, 1), (3, 2, 3), (5, 8, 1), (1000, 8, 8), (1003, 3, 7), (2051, 8, 8), (34848, 8, 8),
+               (4099, 5, 4099), (70001, 17, 8), (307200, 8, 8), (9, 64, 2), (65536 + 13, 4, 1), (8197, 16, 3)]
+
+
+@pytest.mark.parametrize("n,P,S", DENSE_CASES)
+def test_dense_integer_inputs_bit_exact(n, P, S):
+    d = inputs.dense_layer_integer(n, P, seed=n % 101)
+    W, Mom = dev(d["W"]), dev(d["Mom"])
+    psd.sync_dense_ps([dev(g) for g in d["G"]], W, Mom, 0.125, 0.5, S)
+    torch.cuda.synchronize()
+    Wr, Mr = orc.sync_dense_ps(d["G"], d["W"], d["Mom"], 0.125, 0.5, S)
+    assert np.array_equal(W.cpu().numpy(), Wr) and np.array_equal(Mom.cpu().numpy(), Mr)
+
+
+@pytest.mark.parametrize("n,P,S", [(34848, 8, 8), (884736, 8, 8), (100003, 3, 5)])
+def test_dense_gaussian(n, P, S):
+    d = inputs.dense_layer(n, P, seed=n % 103, mom_std=1e-3)
+    W, Mom = dev(d["W"]), dev(d["Mom"])
+    psd.sync_dense_ps([dev(g) for g in d["G"]], W, Mom, inputs.LR, inputs.MU, S)
+    torch.cuda.synchronize()
+    Wr, Mr = orc.sync_dense_ps(d["G"], d["W"], d["Mom"], inputs.LR, inputs.MU, S)
+    e = three_errors(d["W"], W.cpu().numpy(), Mom.cpu().numpy(), Wr, Mr)
+    assert max(e) <= TOL_F32, e
+
+
+def test_dense_sharding_does_not_change_bits():
+    d = inputs.dense_layer(50021, 8, seed=77, mom_std=1e-3)
+    G = [dev(g) for g in d["G"]]
+    outs = []
+    for S in (1, 2, 8, 13, 50021):
+        W, Mom = dev(d["W"]), dev(d["Mom"])
+        psd.sync_dense_ps(G, W, Mom, inputs.LR, inputs.MU, S)
+        torch.cuda.synchronize()
+        outs.append((W.cpu().numpy(), Mom.cpu().numpy()))
+    for w, m in outs[1:]:
+        assert np.array_equal(w, outs[0][0]) and np.array_equal(m, outs[0][1])
+
+
+def test_dense_multi_equals_single_calls():
+    sizes = inputs.conv_sizes() + [0, 5]
+    layers, refs = [], []
+    for i, n in enumerate(sizes):
+        d = inputs.dense_layer_integer(n, 8 if i % 2 == 0 else 3, seed=200 + i)
+        W, Mom = dev(d["W"]), dev(d["Mom"])
+        S = 8 if n >= 8 else 1
+        layers.append(([dev(g) for g in d["G"]], W, Mom, S))
+        refs.append(orc.sync_dense_ps(d["G"], d["W"], d["Mom"], 0.25, 0.5, S))
+    psd.sync_dense_ps_multi(layers, 0.25, 0.5)
+    torch.cuda.synchronize()
+    for (G, W, Mom, S), (Wr, Mr) in zip(layers, refs):
+        assert np.array_equal(W.cpu().numpy(), Wr) and np.array_equal(Mom.cpu().numpy(), Mr)
+
+
+# ---------------------------------------------------------------------------------------
+# SFB reconstruct + update
+# ---------------------------------------------------------------------------------------
+SFB_INT_SHAPES = [  # M, N, B, P  (K = P*B): ragged tiles, K tails, K = 1, odd widths
+    (256, 128, 32, 4), (1, 1, 1, 1), (7, 5, 1, 1), (130, 129, 3, 5), (384, 1000, 16, 8), (257, 300, 5, 3),
+    (512, 21841 // 16, 8, 2), (640, 520, 33, 1), (96, 64, 1, 17),
+]
+
+
+@pytest.mark.parametrize("M,N,B,P", SFB_INT_SHAPES)
+@pytest.mark.parametrize("dtype", [psd.F32, psd.BF16])
+def test_sfb_integer_factors_bit_exact(M, N, B, P, dtype):
+    d = inputs.fc_layer_integer(M, N, B, P, seed=M + N)
+    Wg, Mg, _ = run_sfb(d, dtype, 0.25, 0.5)
+    U, V = orc.pack_factors(d["delta"], d["act"])
+    Wr, Mr = orc.sync_fc_sfb(U, V, d["W"], d["Mom"], 0.25, 0.5)
+    assert np.array_equal(Mg, Mr), np.argwhere(Mg != Mr)[:8]
+    assert np.array_equal(Wg, Wr)
+
+
+def test_sfb_single_sample_is_exact_outer_product():
+    d = inputs.fc_layer(M=200, N=150, B=1, P=1, seed=5)
+    d["Mom"][:] = 0
+    Wg, Mg, _ = run_sfb(d, psd.F32, 1.0, 0.0)
+    want = d["delta"][0].T.astype(np.float32) * d["act"][0].astype(np.float32)   # one product per element
+    assert np.array_equal(Mg, want.astype(np.float32))
+
+
+@pytest.mark.parametrize("cfg", [1, 2])
+def test_sfb_fp32_configs(cfg):
+    d = inputs.fc_config(cfg)
+    Wg, Mg, _ = run_sfb(d, psd.F32, inputs.LR, inputs.MU)
+    U, V = orc.pack_factors(d["delta"], d["act"])
+    Wr, Mr = orc.sync_fc_sfb(U, V, d["W"], d["Mom"], inputs.LR, inputs.MU)
+    e = three_errors(d["W"], Wg, Mg, Wr, Mr)
+    assert max(e) <= TOL_F32, e
+    # second step on top of the first: momentum buffer is now non-zero
+    d2 = dict(d, W=Wg, Mom=Mg)
+    Wg2, Mg2, _ = run_sfb(d2, psd.F32, inputs.LR, inputs.MU)
+    Wr2, Mr2 = orc.sync_fc_sfb(U, V, Wg, Mg, inputs.LR, inputs.MU)
+    e = three_errors(Wg, Wg2, Mg2, Wr2, Mr2)
+    assert max(e) <= TOL_F32, e
+
+
+def test_sfb_bf16_small_gaussian_both_bars():
+    d = inputs.fc_layer(M=700, N=333, B=24, P=5, seed=21, mom_std=1e-4)
+    Wg, Mg, _ = run_sfb(d, psd.BF16, inputs.LR, inputs.MU)
+    Ub, Vb = orc.pack_factors(d["delta"], d["act"], "bf16")
+    Wr, Mr = orc.sync_fc_sfb(Ub, Vb, d["W"], d["Mom"], inputs.LR, inputs.MU)
+    e = three_errors(d["W"], Wg, Mg, Wr, Mr)
+    assert max(e) <= TOL_F32, e
+    U, V = orc.pack_factors(d["delta"], d["act"])
+    Wr, Mr = orc.sync_fc_sfb(U, V, d["W"], d["Mom"], inputs.LR, inputs.MU)
+    e = three_errors(d["W"], Wg, Mg, Wr, Mr)
+    assert max(e) <= TOL_BF16_VS_F32, e
+
+
+def _sample_positions(N, M, count, seed):
+    rng = np.random.default_rng(seed)
+    idx_n = rng.integers(0, N, count)
+    idx_m = rng.integers(0, M, count)
+    # always include the corners and the last row / column (ragged tiles)
+    idx_n[:4] = [0, 0, N - 1, N - 1]
+    idx_m[:4] = [0, M - 1, 0, M - 1]
+    idx_n[4:4 + 64] = N - 1
+    idx_m[64 + 4:64 + 68] = M - 1
+    return idx_n, idx_m
+
+
+@pytest.mark.parametrize("cfg", [3, 4])
+def test_sfb_bf16_full_size_sampled(cfg):
+    """Configs 3 and 4 at full size, in the launch shape the benchmark times; the oracle
+    evaluates 30 000 sampled outputs one by one (plus, for the softmax errors of config 4,
+    the zero column-sum property over whole columns)."""
+    d = inputs.fc_config(cfg)
+    N, M = d["N"], d["M"]
+    Wg, Mg, _ = run_sfb(d, psd.BF16, inputs.LR, inputs.MU)
+    idx_n, idx_m = _sample_positions(N, M, 30000, seed=cfg)
+    W0s, M0s = d["W"][idx_n, idx_m], d["Mom"][idx_n, idx_m]
+    Ub, Vb = orc.pack_factors(d["delta"], d["act"], "bf16")
+    dWs = orc.rebuild_samples(Ub, Vb, idx_n, idx_m)
+    Wr, Mr = orc.momentum_update(dWs, W0s, M0s, inputs.LR, inputs.MU)
+    e = three_errors(W0s, Wg[idx_n, idx_m], Mg[idx_n, idx_m], Wr, Mr)
+    assert max(e) <= TOL_F32, e
+    U, V = orc.pack_factors(d["delta"], d["act"])
+    dWs = orc.rebuild_samples(U, V, idx_n, idx_m)
+    Wr, Mr = orc.momentum_update(dWs, W0s, M0s, inputs.LR, inputs.MU)
+    e = three_errors(W0s, Wg[idx_n, idx_m], Mg[idx_n, idx_m], Wr, Mr)
+    assert max(e) <= TOL_BF16_VS_F32, e
+    # every element was touched exactly once: Mom started at zero, W' = W - Mom' holds in fp32
+    assert np.array_equal(Wg, d["W"] - Mg)
+    if cfg == 4:
+        # rows of (softmax - onehot) sum to zero, so each column of dW sums to ~0
+        col = Mg.astype(np.float64).sum(axis=0)
+        assert np.abs(col).max() <= 2e-2 * np.abs(Mg.astype(np.float64)).sum(axis=0).max()
+
+
+def test_sfb_equals_ps_route_on_the_same_gradients():
+    # Section 4.3.1: factors reconstruct the gradient exactly, so both routes agree
+    d = inputs.fc_layer_integer(M=300, N=200, B=4, P=3, seed=31)
+    Wg, Mg, _ = run_sfb(d, psd.F32, 0.25, 0.5)
+    G = [dev((d["delta"][p].astype(np.float64).T @ d["act"][p].astype(np.float64)).astype(np.float32).ravel())
+         for p in range(3)]
+    W, Mom = dev(d["W"].ravel()), dev(d["Mom"].ravel())
+    psd.sync_dense_ps(G, W, Mom, 0.25, 0.5, 8)
+    torch.cuda.synchronize()
+    assert np.array_equal(W.cpu().numpy(), Wg.ravel()) and np.array_equal(Mom.cpu().numpy(), Mg.ravel())
+
+
+# ---------------------------------------------------------------------------------------
+# whole iteration (config 5): routes, issue order, per-layer parity
+# ---------------------------------------------------------------------------------------
+def _build_iteration(layers, factor_dtype, streams):
+    tasks, state = [], []
+    for L, st in zip(layers, streams):
+        if L["kind"] == "conv":
+            plan = psd.plan_layer(psd.LAYER_CONV, L["n"], 1, inputs.CNN_B, L["P"])
+            W, Mom = dev(L["W"]), dev(L["Mom"])
+            tasks.append(dict(plan=plan, G=[dev(g) for g in L["G"]], S=min(inputs.CNN_S, L["n"]), W=W, Mom=Mom,
+                              stream=st))
+        else:
+            plan = psd.plan_layer(psd.LAYER_FC, L["M"], L["N"], L["B"], L["P"])
+            U, ldu, V, ldv = psd.alloc_factors(plan, factor_dtype, DEV)
+            W, Mom = dev(L["W"]), dev(L["Mom"])
+            tasks.append(dict(plan=plan, factor_dtype=factor_dtype, delta=[dev(x) for x in L["delta"]],
+                              act=[dev(x) for x in L["act"]], U=U, ldu=ldu, V=V, ldv=ldv, W=W, Mom=Mom, stream=st))
+        state.append((W, Mom))
+    return tasks, state
+
+
+@pytest.mark.parametrize("factor_dtype", [psd.F32, psd.BF16])
+def test_iteration_scaled_down_matches_oracle_and_ignores_issue_order(factor_dtype):
+    layers = inputs.cnn_iteration(scale=8, B=16, P=4)
+    results = []
+    for order in ("own_streams", "one_stream", "reversed_list"):
+        streams = [torch.cuda.Stream(device=DEV) for _ in layers] if order != "one_stream" else [None] * len(layers)
+        tasks, state = _build_iteration(layers, factor_dtype, streams)
+        torch.cuda.synchronize()
+        if order == "reversed_list":
+            # give the library the layers in the opposite order: a different issue sequence,
+            # which must not matter because layers own disjoint parameters (Section 4.2)
+            psd.Iteration(tasks[::-1]).run(inputs.LR, inputs.MU, psd.RULE_ALG3)
+        else:
+            psd.Iteration(tasks).run(inputs.LR, inputs.MU, psd.RULE_ALG3)
+        torch.cuda.synchronize()
+        results.append([(W.cpu().numpy(), Mom.cpu().numpy()) for W, Mom in state])
+    for other in results[1:]:
+        for (w0, m0), (w1, m1) in zip(results[0], other):
+            assert np.array_equal(w0, w1) and np.array_equal(m0, m1)
+    name = "f32" if factor_dtype == psd.F32 else "bf16"
+    for L, (Wg, Mg) in zip(layers, results[0]):
+        if L["kind"] == "conv":
+            Wr, Mr = orc.sync_dense_ps(L["G"], L["W"], L["Mom"], inputs.LR, inputs.MU, min(inputs.CNN_S, L["n"]))
+        else:
+            U, V = orc.pack_factors(L["delta"], L["act"], name)
+            Wr, Mr = orc.sync_fc_sfb(U, V, L["W"], L["Mom"], inputs.LR, inputs.MU)
+        e = three_errors(L["W"], Wg, Mg, Wr, Mr)
+        assert max(e) <= TOL_F32, (L["name"], e)
+
+
+def test_iteration_routes_follow_the_plan():
+    # fc8-shaped layer at P=8, B=256: Algorithm 3 says SF_PS, the prose rule says SFB; both
+    # run the reconstruction.  A layer whose route is PS_DENSE but has no dense copies is refused.
+    plan = psd.plan_layer(psd.LAYER_FC, 4096, 1000, 256, 8)
+    assert psd.ROUTE_NAMES[plan.route_alg3] == "SF_PS" and psd.ROUTE_NAMES[plan.route_vs_dense] == "SFB"
+    d = inputs.fc_layer(64, 32, 256, 16, seed=9)        # tiny layer, huge batch: vs-dense rule -> PS_DENSE
+    plan = psd.plan_layer(psd.LAYER_FC, 64, 32, 256, 16)
+    assert plan.route_vs_dense == psd.ROUTE_PS_DENSE and plan.route_alg3 == psd.ROUTE_SF_PS
+    U, ldu, V, ldv = psd.alloc_factors(plan, psd.F32, DEV)
+    task = dict(plan=plan, factor_dtype=psd.F32, delta=[dev(x) for x in d["delta"]], act=[dev(x) for x in d["act"]],
+                U=U, ldu=ldu, V=V, ldv=ldv, W=dev(d["W"]), Mom=dev(d["Mom"]), stream=None)
+    with pytest.raises(psd.PsdError) as ei:
+        psd.Iteration([task]).run(inputs.LR, inputs.MU, psd.RULE_SFB_VS_DENSE)
+    assert ei.value.status == psd.E_UNSUPPORTED
+    # with the dense copies present the PS route runs and equals the SFB result
+    G = [dev((d["delta"][p].astype(np.float64).T @ d["act"][p].astype(np.float64)).astype(np.float32).ravel())
+         for p in range(16)]
+    W2, Mom2 = dev(d["W"]), dev(d["Mom"])
+    psd.Iteration([dict(task, G=G, S=4, W=W2, Mom=Mom2)]).run(inputs.LR, inputs.MU, psd.RULE_SFB_VS_DENSE)
+    psd.Iteration([task]).run(inputs.LR, inputs.MU, psd.RULE_ALG3)
+    torch.cuda.synchronize()
+    assert orc.rel_frob(Mom2.cpu().numpy(), task["Mom"].cpu().numpy()) <= TOL_F32
