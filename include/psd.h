@@ -143,6 +143,9 @@ typedef struct psd_layer_task {
                                   NULL for an FC layer that is routed to SFB / SF_PS) */
     float* W; float* Mom;      /* [dev] N x M fp32 */
     void* stream;              /* the stream this layer's work is enqueued on */
+    void* ev_begin;            /* optional hipEvent_t (or NULL) recorded on `stream` right before */
+    void* ev_end;              /* ... and right after the layer's reconstruct+update or
+                                  sum+update kernel (factor packing lies outside the pair) */
 } psd_layer_task;
 
 /* One iteration's synchronisation in the order of Algorithm 2: layers are given bottom-up

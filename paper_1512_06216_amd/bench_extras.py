@@ -1,0 +1,102 @@
+"""Optional per-configuration timings for bench.py --extras: the four single-layer FC
+configurations (pack and reconstruct+update timed separately) and a size sweep of the
+dense parameter-server kernel.  Timing only: no arithmetic of the method lives here."""
+from __future__ import annotations
+
+import numpy as np
+
+PEAK_HBM_GBS = 8000.0
+PEAK_TF = {"bf16": 2500.0, "f32": 157.3}
+
+
+def _time_ms(torch, fn, n_sets, iters=20, warmup=3):
+    """Mean milliseconds per call of fn(set_index), rotating over n_sets buffer sets."""
+    for i in range(warmup):
+        fn(i % n_sets)
+    torch.cuda.synchronize()
+    a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    a.record()
+    for i in range(iters):
+        fn(i % n_sets)
+    b.record()
+    torch.cuda.synchronize()
+    return a.elapsed_time(b) / iters
+
+
+def fc_config(psd, inputs, torch, dev, cfg_id, dtype_name=None, working_set_mb=600):
+    c = inputs.FC_CONFIGS[cfg_id]
+    dtype_name = dtype_name or c["factor_dtype"]
+    dtype = psd.BF16 if dtype_name == "bf16" else psd.F32
+    d = inputs.fc_config(cfg_id)
+    M, N, B, P = d["M"], d["N"], d["B"], d["P"]
+    K = P * B
+    es = 2 if dtype_name == "bf16" else 4
+    plan = psd.plan_layer(psd.LAYER_FC, M, N, B, P)
+    per_set = 8 * N * M + K * (M + N) * (4 + es)
+    n_sets = int(min(16, max(2, np.ceil(working_set_mb * 1e6 / per_set))))
+    sets = []
+    for _ in range(n_sets):
+        U, ldu, V, ldv = psd.alloc_factors(plan, dtype, dev)
+        sets.append(dict(delta=[torch.from_numpy(x).to(dev) for x in d["delta"]],
+                         act=[torch.from_numpy(x).to(dev) for x in d["act"]], U=U, ldu=ldu, V=V, ldv=ldv,
+                         W=torch.from_numpy(d["W"]).to(dev), Mom=torch.from_numpy(d["Mom"]).to(dev)))
+
+    def pack(i):
+        s = sets[i]
+        psd.pack_factors(plan, s["delta"], s["act"], dtype, s["U"], s["ldu"], s["V"], s["ldv"])
+
+    def sfb(i):
+        s = sets[i]
+        psd.sync_fc_sfb(plan, dtype, s["U"], s["ldu"], s["V"], s["ldv"], s["W"], s["Mom"], inputs.LR, inputs.MU)
+
+    def both(i):
+        pack(i)
+        sfb(i)
+
+    for i in range(n_sets):
+        pack(i)
+    t_pack = _time_ms(torch, pack, n_sets)
+    t_sfb = _time_ms(torch, sfb, n_sets)
+    t_both = _time_ms(torch, both, n_sets)
+    flops = 2 * N * M * K
+    bytes_sfb = 16 * N * M + K * (M + N) * es
+    bytes_pack = K * (M + N) * (4 + es)
+    return dict(config=cfg_id, name=c["name"], M=M, N=N, B=B, P=P, K=K, factor_dtype=dtype_name, rotating_sets=n_sets,
+                route_alg3=psd.ROUTE_NAMES[plan.route_alg3], route_vs_dense=psd.ROUTE_NAMES[plan.route_vs_dense],
+                sfb_ms=round(t_sfb, 5), sfb_TFLOPs=round(flops / t_sfb / 1e9, 2),
+                sfb_frac_mfma=round(flops / t_sfb / 1e9 / PEAK_TF[dtype_name], 4),
+                sfb_GBps=round(bytes_sfb / t_sfb / 1e6, 1), sfb_frac_hbm=round(bytes_sfb / t_sfb / 1e6 / PEAK_HBM_GBS, 4),
+                pack_ms=round(t_pack, 5), pack_GBps=round(bytes_pack / t_pack / 1e6, 1),
+                pack_plus_sfb_ms=round(t_both, 5), pack_plus_sfb_TFLOPs=round(flops / t_both / 1e9, 2))
+
+
+def dense_sweep(psd, inputs, torch, dev, sizes=(2332704, 16777216, 37748736, 89460736), P=8, S=8):
+    out = []
+    for n in sizes:
+        per_set = n * (4 * P + 8)
+        n_sets = int(min(8, max(2, np.ceil(1.2e9 / per_set))))
+        sets = []
+        for _ in range(n_sets):
+            G = [torch.randn(n, device=dev) * 1e-3 for _ in range(P)]
+            sets.append((G, torch.randn(n, device=dev) * 1e-2, torch.zeros(n, device=dev)))
+
+        def run(i):
+            G, W, Mom = sets[i]
+            psd.sync_dense_ps(G, W, Mom, inputs.LR, inputs.MU, S)
+
+        t = _time_ms(torch, run, n_sets)
+        b = n * (4 * P + 16)
+        out.append(dict(n=n, P=P, S=S, rotating_sets=n_sets, ms=round(t, 5), GBps=round(b / t / 1e6, 1),
+                        frac_hbm=round(b / t / 1e6 / PEAK_HBM_GBS, 4)))
+        del sets
+        torch.cuda.empty_cache()
+    return out
+
+
+def run(psd, inputs, torch, dev):
+    res = {"fc": [], "dense_sweep": None}
+    for cfg, dt in [(1, "f32"), (2, "f32"), (2, "bf16"), (3, "bf16"), (3, "f32"), (4, "bf16")]:
+        res["fc"].append(fc_config(psd, inputs, torch, dev, cfg, dt))
+        torch.cuda.empty_cache()
+    res["dense_sweep"] = dense_sweep(psd, inputs, torch, dev)
+    return res

@@ -12,7 +12,7 @@ import os
 import torch
 
 _PKG = os.path.dirname(os.path.abspath(__file__))
-LIB_PATH = os.path.join(_PKG, "libpsd.so")
+LIB_PATH = os.path.join(_PKG, os.environ.get("PSD_LIB_NAME", "libpsd.so"))
 
 OK, E_INVALID, E_NULL, E_UNSUPPORTED, E_OVERFLOW, E_HIP = 0, -1, -2, -3, -4, -5
 LAYER_CONV, LAYER_FC = 0, 1
@@ -49,7 +49,8 @@ class LayerTask(ctypes.Structure):
     _fields_ = [("plan", Plan), ("factor_dtype", ctypes.c_int32), ("S", ctypes.c_int32),
                 ("delta_p", _f32pp), ("act_p", _f32pp),
                 ("U", ctypes.c_void_p), ("ldu", ctypes.c_int64), ("V", ctypes.c_void_p), ("ldv", ctypes.c_int64),
-                ("G", _f32pp), ("W", _f32p), ("Mom", _f32p), ("stream", ctypes.c_void_p)]
+                ("G", _f32pp), ("W", _f32p), ("Mom", _f32p), ("stream", ctypes.c_void_p),
+                ("ev_begin", ctypes.c_void_p), ("ev_end", ctypes.c_void_p)]
 
 
 class PsdError(RuntimeError):
@@ -214,6 +215,7 @@ class Iteration:
 
     Each layer is a dict: FC  -> plan, factor_dtype, delta, act, U, ldu, V, ldv, W, Mom, stream
                          conv -> plan, G, S, W, Mom, stream
+    plus optional ev_begin / ev_end (raw hipEvent_t handles as ints).
     Building it does no device work; run() makes the single library call.
     """
 
@@ -228,6 +230,7 @@ class Iteration:
             t.W = ctypes.cast(_dev_ptr(L["W"], torch.float32, n, "W"), _f32p)
             t.Mom = ctypes.cast(_dev_ptr(L["Mom"], torch.float32, n, "Mom"), _f32p)
             t.stream = _stream_handle(L.get("stream"))
+            t.ev_begin, t.ev_end = L.get("ev_begin"), L.get("ev_end")   # raw hipEvent_t handles or None
             t.S = L.get("S", 1)
             t.factor_dtype = L.get("factor_dtype", F32)
             if L.get("G") is not None:

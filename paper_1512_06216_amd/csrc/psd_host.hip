@@ -206,6 +206,7 @@ psd_status psd_sync_iteration(int32_t L, const psd_layer_task* layers, float lr,
     for (int32_t l = L - 1; l >= 0; --l) {
         const psd_layer_task& t = layers[l];
         const int32_t route = rule == PSD_RULE_ALG3 ? t.plan.route_alg3 : t.plan.route_vs_dense;
+        hipStream_t st = static_cast<hipStream_t>(t.stream);
         psd_status r;
         if (route == PSD_ROUTE_PS_DENSE) {
             if (!t.G) return PSD_E_UNSUPPORTED;   // route needs dense gradient copies
@@ -213,17 +214,20 @@ psd_status psd_sync_iteration(int32_t L, const psd_layer_task* layers, float lr,
             if (mul_u64(static_cast<uint64_t>(t.plan.M), static_cast<uint64_t>(t.plan.N), &n) ||
                 n > (uint64_t(1) << 40))
                 return PSD_E_INVALID;
+            if (t.ev_begin) PSD_HIP_TRY(hipEventRecord(static_cast<hipEvent_t>(t.ev_begin), st));
             r = psd_sync_dense_ps(static_cast<int64_t>(n), static_cast<int32_t>(t.plan.P), t.G, t.W, t.Mom,
                                   lr, mu, t.S, t.stream);
         } else if (route == PSD_ROUTE_SFB || route == PSD_ROUTE_SF_PS) {
             if (t.plan.kind != PSD_LAYER_FC) return PSD_E_INVALID;
             r = psd_pack_factors(&t.plan, t.delta_p, t.act_p, t.factor_dtype, t.U, t.ldu, t.V, t.ldv, t.stream);
+            if (r == PSD_OK && t.ev_begin) PSD_HIP_TRY(hipEventRecord(static_cast<hipEvent_t>(t.ev_begin), st));
             if (r == PSD_OK)
                 r = psd_sync_fc_sfb(&t.plan, t.factor_dtype, t.U, t.ldu, t.V, t.ldv, t.W, t.Mom, lr, mu, t.stream);
         } else {
             return PSD_E_INVALID;
         }
         if (r != PSD_OK) return r;
+        if (t.ev_end) PSD_HIP_TRY(hipEventRecord(static_cast<hipEvent_t>(t.ev_end), st));
     }
     return PSD_OK;
 }
