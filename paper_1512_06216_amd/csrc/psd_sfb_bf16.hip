@@ -2,15 +2,19 @@
 // fp32 W / Mom (Section 4.3.1 step 3, Eq. 5; Algorithm 3's update line):
 //     dW[n][m] = sum_k U[k][n] * V[k][m] ;  Mom = mu*Mom + lr*dW ;  W = W - Mom
 //
-// The contraction index k is the OUTER dimension of both stacked factor matrices, while
-// v_mfma_f32_32x32x16_bf16 wants 8 consecutive k in one lane.  The tiles are copied to LDS
-// as they are (K-outer, 16-byte chunks) and read back with gfx950's transposing LDS load
-// (ds_read_b64_tr_b16): a 16-lane group reads four k rows x 16 columns and each lane ends
-// up with the 4 k values of its own column.
+// Layout problem.  The contraction index k is the OUTER dimension of both stacked factor
+// matrices, while v_mfma_f32_32x32x16_bf16 wants 8 consecutive k in one lane.  Tiles are
+// copied to LDS as they are (K-outer, 16-byte chunks) and read back with gfx950's
+// transposing LDS load (ds_read_b64_tr_b16): a 16-lane group reads four k rows x 16 columns
+// and each lane ends up with the 4 k values of its own column.
 //
-// Pipeline: global loads run two k-stages ahead of the MFMAs (two register stages, two
-// LDS buffers, one barrier per stage), because one stage of MFMA work (~0.4 us) is shorter
-// than a loaded HBM/L2 round trip.
+// Feeding the MFMA pipe.  One k-stage of MFMA work (~0.4 us) is much shorter than a loaded
+// L2/HBM round trip (>1 us at the tail), so the tiles travel global -> LDS without passing
+// through registers (buffer_load_dwordx4 ... lds) and NSTAGE-1 stages are kept in flight in
+// an NSTAGE-deep ring of LDS buffers.  The DMA writes whole 1 KiB runs, so rows cannot be
+// padded; bank conflicts of the transposing reads are avoided by XOR-swizzling the 16-byte
+// chunk index of a row with its row number instead.  Rows past the end of K are zero-filled
+// by the buffer range check, so there is no tail code.
 //
 // MFMA operand roles are swapped (rows = m, columns = n) so that the four consecutive
 // accumulator rows a lane owns are four adjacent m of one W row; the epilogue turns each
@@ -24,45 +28,62 @@ namespace {
 typedef float f32x16 __attribute__((ext_vector_type(16)));
 typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef int i32x4 __attribute__((ext_vector_type(4)));
+typedef __attribute__((address_space(3))) bf16x4 lds_bf16x4;
 
 constexpr int KT = 32;         // k rows per LDS stage (two MFMA k-steps of 16)
-constexpr int PAD = 16;        // bf16 elements of row padding: row stride = 32 bytes mod 128,
-                               // so the 4 rows one 16-lane group reads fall in distinct banks
 constexpr int GROUP_N = 8;     // tile rows per raster group (L2 reuse of the V panels)
+constexpr int PLD = 36;        // epilogue patch row stride in floats (144 B: conflict-free)
 
-// WN x WM wavefronts, each owning BN x BM MFMA blocks of 32 x 32; OCC = wavefronts per SIMD
-template <int WN_, int WM_, int BN_, int BM_, int OCC_>
+// WN x WM wavefronts, each owning BN x BM MFMA blocks of 32 x 32; NSTAGE LDS buffers;
+// OCC = wavefronts per SIMD the register budget is sized for
+template <int WN_, int WM_, int BN_, int BM_, int NSTAGE_, int OCC_>
 struct Cfg {
-    static constexpr int WN = WN_, WM = WM_, BN = BN_, BM = BM_, OCC = OCC_;
-    static constexpr int THREADS = 64 * WN * WM;
+    static constexpr int WN = WN_, WM = WM_, BN = BN_, BM = BM_, NSTAGE = NSTAGE_, OCC = OCC_;
+    static constexpr int WAVES = WN * WM, THREADS = 64 * WAVES;
     static constexpr int TN = 32 * BN * WN, TM = 32 * BM * WM;   // workgroup tile
-    static constexpr int LDA = TN + PAD, LDB = TM + PAD;         // LDS row strides (elements)
-    static constexpr int A_ELEMS = KT * LDA, B_ELEMS = KT * LDB;
-    static constexpr int CPR_A = TN / 8, CPR_B = TM / 8;         // 16-byte chunks per tile row
-    static constexpr int CH_A = KT * CPR_A / THREADS, CH_B = KT * CPR_B / THREADS;
-    static constexpr size_t LDS_BYTES = size_t(2) * (A_ELEMS + B_ELEMS) * 2;
-    static_assert(KT * CPR_A % THREADS == 0 && KT * CPR_B % THREADS == 0, "tile rows must split evenly");
+    static constexpr int RA = TN * 2, RB = TM * 2;               // LDS row bytes (U tile, V tile)
+    static constexpr int A_BYTES = KT * RA, B_BYTES = KT * RB, STAGE_BYTES = A_BYTES + B_BYTES;
+    static constexpr int NI_A = A_BYTES / 1024 / WAVES;          // 1 KiB DMA instructions per wavefront
+    static constexpr int NI_B = B_BYTES / 1024 / WAVES;
+    static constexpr int PATCH_BYTES = WAVES * 32 * PLD * 4;
+    static constexpr size_t LDS_BYTES =
+        size_t(NSTAGE) * STAGE_BYTES > size_t(PATCH_BYTES) ? size_t(NSTAGE) * STAGE_BYTES : size_t(PATCH_BYTES);
+    static_assert(A_BYTES % (1024 * WAVES) == 0 && B_BYTES % (1024 * WAVES) == 0, "stage must split into 1 KiB runs");
+    static_assert(RA >= 128 && RB >= 128, "swizzle needs rows of at least 128 bytes");
+    static_assert(NSTAGE >= 3, "the pipeline keeps at least one stage in flight beyond the one being awaited");
 };
 
-typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
-
-// Buffer descriptor over a whole stacked factor matrix (K * ld bf16).  Loads through it are
-// range-checked by the hardware: a 16-byte chunk at or beyond `bytes` returns zeros, which
-// is what the k tail of the last stage needs, with no branch in the loop.
-__device__ __forceinline__ __amdgpu_buffer_rsrc_t factor_rsrc(const uint16_t* X, uint32_t bytes)
+// global -> LDS, 16 bytes per lane: lane i's chunk lands at lds_addr + 16*i.  A lane whose
+// offset is at or past the descriptor's size writes zeros.
+__device__ __forceinline__ void dma_b128(uint32_t lds_addr_uniform, uint32_t voff, i32x4 rsrc)
 {
-    return __builtin_amdgcn_make_buffer_rsrc(const_cast<uint16_t*>(X), 0, static_cast<int>(bytes), 0x00020000);
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tbuffer_load_dwordx4 %1, %2, 0 offen lds"
+                 :
+                 : "s"(lds_addr_uniform), "v"(voff), "s"(rsrc)
+                 : "memory");
 }
 
-// Transposing read of a (4 k) x (16 columns) patch whose top-left element is `patch`.
-// Lane L of a 16-lane group supplies the address of 4 adjacent columns in row (L%16)/4,
-// starting at column 4*(L%4); afterwards lane i of the group holds rows 0..3 of column i.
-__device__ __forceinline__ bf16x4 read_tr(const uint16_t* patch, int ld_elems, int lane)
+template <int N>
+__device__ __forceinline__ void wait_vmcnt()
 {
-    const int l16 = lane & 15;
-    const uint16_t* p = patch + (l16 >> 2) * ld_elems + 4 * (l16 & 3);
-    return __builtin_amdgcn_ds_read_tr16_b64_v4bf16(
-        (__attribute__((address_space(3))) bf16x4*)(p));
+    asm volatile("s_waitcnt vmcnt(%0)" : : "n"(N) : "memory");
+}
+
+__device__ __forceinline__ i32x4 factor_rsrc(const uint16_t* X, uint32_t bytes)
+{
+    const uint64_t a = reinterpret_cast<uint64_t>(X);
+    i32x4 r;
+    r.x = static_cast<int>(a & 0xffffffffu);
+    r.y = static_cast<int>((a >> 32) & 0xffffu);      // stride 0: raw buffer, byte-granular range check
+    r.z = static_cast<int>(bytes);
+    r.w = 0x00020000;
+    return r;
+}
+
+__device__ __forceinline__ bf16x4 read_tr(uint32_t lds_addr)
+{
+    return __builtin_amdgcn_ds_read_tr16_b64_v4bf16(reinterpret_cast<lds_bf16x4*>(lds_addr));
 }
 
 __device__ __forceinline__ void upd(float d, float& w, float& mo, float lr, float mu)
@@ -71,15 +92,37 @@ __device__ __forceinline__ void upd(float d, float& w, float& mo, float lr, floa
     w = w - mo;
 }
 
+// Scheduling pattern for one pipeline phase holding MF MFMAs and R LDS reads that do not depend
+// on each other: 1 MFMA, then its share of the reads, and so on.
+template <int R, int MF, int I = 0>
+__device__ __forceinline__ void interleave_groups()
+{
+    if constexpr (I < MF) {
+        __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);                    // one MFMA
+        constexpr int n = R * (I + 1) / MF - R * I / MF;
+        if constexpr (n > 0) __builtin_amdgcn_sched_group_barrier(0x100, n, 0);  // n DS reads
+        interleave_groups<R, MF, I + 1>();
+    }
+}
+
 template <class C>
 __global__ void __launch_bounds__(C::THREADS, C::OCC)
 sfb_bf16_kernel(const uint16_t* __restrict__ U, int64_t ldu, const uint16_t* __restrict__ V, int64_t ldv,
                 float* __restrict__ W, float* __restrict__ Mom, int N, int M, int K, float lr, float mu,
-                int tiles_n, int tiles_m, uint32_t u_bytes, uint32_t v_bytes)
+                int tiles_n, int tiles_m, uint32_t u_bytes, uint32_t v_bytes, int first_round, int stagger_naps)
 {
-    extern __shared__ __attribute__((aligned(16))) uint16_t lds[];
-    uint16_t* As = lds;                        // [2][KT][LDA]   U tile (n columns)
-    uint16_t* Bs = lds + 2 * C::A_ELEMS;       // [2][KT][LDB]   V tile (m columns)
+    extern __shared__ __attribute__((aligned(1024))) uint16_t lds[];
+    // Workgroups that start together run in lock step: all in the MFMA loop (HBM idle), then all in
+    // the W/Mom epilogue (MFMA idle).  The workgroups of the first round that sit in the second,
+    // third... wave slot of their SIMDs therefore start late by about one main loop, so that from
+    // then on one resident workgroup's epilogue overlaps the other's main loop.  A sleeping
+    // workgroup costs nothing: its neighbour gets the whole MFMA pipe meanwhile.
+    if (static_cast<int>(blockIdx.x) < first_round) {
+        const unsigned slot = __builtin_amdgcn_s_getreg((3 << 11) | 4);   // HW_ID bits [3:0]: wave slot in its SIMD
+        for (unsigned i = 0; i < slot * static_cast<unsigned>(stagger_naps); ++i) __builtin_amdgcn_s_sleep(100);
+    }
+    const uint32_t lds0 = static_cast<uint32_t>(reinterpret_cast<uintptr_t>(
+        (__attribute__((address_space(3))) void*)lds));
 
     // Workgroup -> tile.  Consecutive workgroup ids go round-robin over the 8 XCDs; give each
     // XCD a contiguous run of the tile sequence, and order that sequence in groups of GROUP_N
@@ -93,9 +136,65 @@ sfb_bf16_kernel(const uint16_t* __restrict__ U, int64_t ldu, const uint16_t* __r
     const int tile_n = g * GROUP_N + in_g % rows_g, tile_m = in_g / rows_g;
 
     const int64_t n0 = int64_t(tile_n) * C::TN, m0 = int64_t(tile_m) * C::TM;
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int wn0 = (wave / C::WM) * 32 * C::BN, wm0 = (wave % C::WM) * 32 * C::BM;
-    const int grp = lane >> 4;                 // 16-lane group: columns +16*(grp%2), k rows +8*(grp/2)
+    const int grp = lane >> 4, l16 = lane & 15;
+
+    // ---- DMA plan: instruction j of this wavefront moves rows [g*RPI, (g+1)*RPI) of a stage,
+    // lane i carrying the chunk that belongs at physical position i of that 1 KiB run.
+    // physical chunk pc of row r holds logical chunk pc ^ ((r & 3) << 1)
+    const i32x4 rsrc_u = factor_rsrc(U, u_bytes), rsrc_v = factor_rsrc(V, v_bytes);
+    uint32_t voff_a[C::NI_A], voff_b[C::NI_B];
+    {
+        constexpr int LPR = C::RA / 16, RPI = 64 / LPR;
+#pragma unroll
+        for (int j = 0; j < C::NI_A; ++j) {
+            const int r = (wave * C::NI_A + j) * RPI + lane / LPR;
+            const int lc = (lane % LPR) ^ ((r & 3) << 1);
+            voff_a[j] = static_cast<uint32_t>((r * ldu + n0 + lc * 8) * 2);
+        }
+    }
+    {
+        constexpr int LPR = C::RB / 16, RPI = 64 / LPR;
+#pragma unroll
+        for (int j = 0; j < C::NI_B; ++j) {
+            const int r = (wave * C::NI_B + j) * RPI + lane / LPR;
+            const int lc = (lane % LPR) ^ ((r & 3) << 1);
+            voff_b[j] = static_cast<uint32_t>((r * ldv + m0 + lc * 8) * 2);
+        }
+    }
+    const uint32_t step_a = static_cast<uint32_t>(KT * ldu * 2), step_b = static_cast<uint32_t>(KT * ldv * 2);
+    auto issue = [&](int t) {                    // stage t -> ring buffer t % NSTAGE
+        const uint32_t base = lds0 + static_cast<uint32_t>(t % C::NSTAGE) * C::STAGE_BYTES;
+#pragma unroll
+        for (int j = 0; j < C::NI_A; ++j)
+            dma_b128(base + (wave * C::NI_A + j) * 1024, voff_a[j] + static_cast<uint32_t>(t) * step_a, rsrc_u);
+#pragma unroll
+        for (int j = 0; j < C::NI_B; ++j)
+            dma_b128(base + C::A_BYTES + (wave * C::NI_B + j) * 1024,
+                     voff_b[j] + static_cast<uint32_t>(t) * step_b, rsrc_v);
+    };
+
+    // ---- transposing-read plan.  A 16-lane group reads a (4 k) x (16 column) patch: lane L
+    // supplies the address of 4 adjacent columns of row (L%16)/4 starting at column 4*(L%4), and
+    // ends up with rows 0..3 of column L%16.  Lane groups: columns +16*(grp%2), k rows +8*(grp/2).
+    // The byte address of this lane's piece inside a stage buffer, for k-step 0, low half:
+    uint32_t rd_a[C::BN], rd_b[C::BM];
+    {
+        const int row = 8 * (grp >> 1) + (l16 >> 2);           // row & 3 == l16 >> 2
+        const int sw = (l16 >> 2) << 1;
+#pragma unroll
+        for (int bn = 0; bn < C::BN; ++bn) {
+            const int chunk = (((wn0 + 32 * bn + 16 * (grp & 1)) >> 3) ^ sw) + ((l16 & 3) >> 1);
+            rd_a[bn] = static_cast<uint32_t>(row * C::RA + chunk * 16 + (l16 & 1) * 8);
+        }
+#pragma unroll
+        for (int bm = 0; bm < C::BM; ++bm) {
+            const int chunk = (((wm0 + 32 * bm + 16 * (grp & 1)) >> 3) ^ sw) + ((l16 & 3) >> 1);
+            rd_b[bm] = static_cast<uint32_t>(C::A_BYTES + row * C::RB + chunk * 16 + (l16 & 1) * 8);
+        }
+    }
 
     f32x16 acc[C::BN][C::BM];
 #pragma unroll
@@ -105,64 +204,18 @@ sfb_bf16_kernel(const uint16_t* __restrict__ U, int64_t ldu, const uint16_t* __r
 #pragma unroll
             for (int r = 0; r < 16; ++r) acc[a][c][r] = 0.f;
 
-    uint4 ra[2][C::CH_A], rb[2][C::CH_B];      // two register stages of prefetched chunks
-    // byte offset of this lane's chunk h inside a stage that starts at row 0; a column past
-    // ld wraps into the next row, which only feeds outputs n >= N (m >= M) that are never stored
-    const __amdgpu_buffer_rsrc_t rsrc_u = factor_rsrc(U, u_bytes), rsrc_v = factor_rsrc(V, v_bytes);
-    uint32_t off_a[C::CH_A], off_b[C::CH_B];
-#pragma unroll
-    for (int h = 0; h < C::CH_A; ++h) {
-        const int c = tid + h * C::THREADS;
-        off_a[h] = static_cast<uint32_t>(((c / C::CPR_A) * ldu + n0 + (c % C::CPR_A) * 8) * 2);
-    }
-#pragma unroll
-    for (int h = 0; h < C::CH_B; ++h) {
-        const int c = tid + h * C::THREADS;
-        off_b[h] = static_cast<uint32_t>(((c / C::CPR_B) * ldv + m0 + (c % C::CPR_B) * 8) * 2);
-    }
-    const uint32_t stage_a = static_cast<uint32_t>(KT * ldu * 2), stage_b = static_cast<uint32_t>(KT * ldv * 2);
-    auto fetch = [&](int st, uint32_t stage) {
-#pragma unroll
-        for (int h = 0; h < C::CH_A; ++h) {
-            const u32x4 v = __builtin_amdgcn_raw_buffer_load_b128(rsrc_u, off_a[h] + stage * stage_a, 0, 0);
-            ra[st][h] = make_uint4(v.x, v.y, v.z, v.w);
-        }
-#pragma unroll
-        for (int h = 0; h < C::CH_B; ++h) {
-            const u32x4 v = __builtin_amdgcn_raw_buffer_load_b128(rsrc_v, off_b[h] + stage * stage_b, 0, 0);
-            rb[st][h] = make_uint4(v.x, v.y, v.z, v.w);
-        }
-    };
-    auto stash = [&](int st, int buf) {
-#pragma unroll
-        for (int h = 0; h < C::CH_A; ++h) {
-            const int c = tid + h * C::THREADS;
-            *reinterpret_cast<uint4*>(As + buf * C::A_ELEMS + (c / C::CPR_A) * C::LDA + (c % C::CPR_A) * 8) = ra[st][h];
-        }
-#pragma unroll
-        for (int h = 0; h < C::CH_B; ++h) {
-            const int c = tid + h * C::THREADS;
-            *reinterpret_cast<uint4*>(Bs + buf * C::B_ELEMS + (c / C::CPR_B) * C::LDB + (c % C::CPR_B) * 8) = rb[st][h];
-        }
-    };
-    const int steps = (K + KT - 1) / KT;
     // this lane's 8 k values of a 16-row MFMA step: ks + 8*(grp/2) + 0..7 (the same for both operands)
-    auto load_frags = [&](int buf, int ks, bf16x8 (&a)[C::BN], bf16x8 (&bb)[C::BM]) {
-        const uint16_t* Ab = As + buf * C::A_ELEMS;
-        const uint16_t* Bb = Bs + buf * C::B_ELEMS;
-        const int krow = ks + 8 * (grp >> 1);
+    auto load_frags = [&](uint32_t base, int ks, bf16x8 (&a)[C::BN], bf16x8 (&bb)[C::BM]) {
 #pragma unroll
         for (int bn = 0; bn < C::BN; ++bn) {
-            const uint16_t* patch = Ab + krow * C::LDA + wn0 + 32 * bn + 16 * (grp & 1);
-            const bf16x4 lo = read_tr(patch, C::LDA, lane);
-            const bf16x4 hi = read_tr(patch + 4 * C::LDA, C::LDA, lane);
+            const bf16x4 lo = read_tr(base + rd_a[bn] + ks * C::RA);
+            const bf16x4 hi = read_tr(base + rd_a[bn] + (ks + 4) * C::RA);
             a[bn] = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
         }
 #pragma unroll
         for (int bm = 0; bm < C::BM; ++bm) {
-            const uint16_t* patch = Bb + krow * C::LDB + wm0 + 32 * bm + 16 * (grp & 1);
-            const bf16x4 lo = read_tr(patch, C::LDB, lane);
-            const bf16x4 hi = read_tr(patch + 4 * C::LDB, C::LDB, lane);
+            const bf16x4 lo = read_tr(base + rd_b[bm] + ks * C::RB);
+            const bf16x4 hi = read_tr(base + rd_b[bm] + (ks + 4) * C::RB);
             bb[bm] = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
         }
     };
@@ -174,35 +227,44 @@ sfb_bf16_kernel(const uint16_t* __restrict__ U, int64_t ldu, const uint16_t* __r
             for (int bm = 0; bm < C::BM; ++bm)
                 acc[bn][bm] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bb[bm], a[bn], acc[bn][bm], 0, 0, 0);
     };
-    // One k-stage: LDS buffer `buf` holds stage t, register set `st` holds stage t+1 (st = (t+1)&1).
-    // Both MFMA steps' operand reads are issued up front so the second hides behind the first
-    // step's MFMAs; the next stage is written to the other LDS buffer between the two steps.
-    // The body is branch-free on purpose: stages past the end of K are fetched as zeros by the
-    // range check and stashed into a buffer nobody reads, which keeps the two register sets'
-    // loads distinguishable for the wait-count logic (the older set is waited for, the newer
-    // one stays in flight).
-    auto stage = [&](int buf, int st, int t) {
-        bf16x8 a0[C::BN], b0[C::BM], a1[C::BN], b1[C::BM];
-load_frags(buf, 0, a0, b0);
-        load_frags(buf, 16, a1, b1);
-        __builtin_amdgcn_sched_barrier(0);     // keep every operand read ahead of the first MFMA
-        mma(a0, b0);
-        stash(st, buf ^ 1);
-        fetch(st, t + 3);
-        mma(a1, b1);
-        __syncthreads();
-    };
 
-    fetch(0, 0);
-    fetch(1, 1);                               // stages beyond K read as zeros (range check)
-    stash(0, 0);
-    fetch(0, 2);
+    const int steps = (K + KT - 1) / KT;
+    constexpr int LPS = C::NI_A + C::NI_B;       // DMA instructions per wavefront per stage
+    auto stage_base = [&](int t) { return lds0 + static_cast<uint32_t>(t % C::NSTAGE) * C::STAGE_BYTES; };
+
+    // Software pipeline (one wavefront may be alone on its SIMD, so it has to overlap with itself):
+    // the operand reads of one MFMA step are always issued before the MFMAs of the step before,
+    // also across the stage boundary, and the barrier sits between the two steps of a stage.
+    //   F0 = step 0 of stage t (read during the previous iteration)
+    //   read F1 = step 1 of stage t | MFMA(F0) | stage t+1 landed? barrier | DMA stage t+NSTAGE-1 |
+    //   read F0 = step 0 of stage t+1 | MFMA(F1)
+    // The barrier tells both that every wavefront's share of stage t+1 is visible and that nobody
+    // still reads stage t-1, whose buffer the new DMA overwrites.  Stages past K are zeros.
+    bf16x8 a0[C::BN], b0[C::BM], a1[C::BN], b1[C::BM];
+#pragma unroll
+    for (int t = 0; t < C::NSTAGE - 1; ++t) issue(t);
+    wait_vmcnt<(C::NSTAGE - 2) * LPS>();
     __syncthreads();
-    const int steps2 = (steps + 1) & ~1;       // an odd count runs one extra all-zero stage
-    for (int t = 0; t < steps2; t += 2) {
-        stage(0, 1, t);
-        stage(1, 0, t + 1);
+    load_frags(stage_base(0), 0, a0, b0);
+    // A wavefront issues at most one LDS instruction per ~16 cycles and one MFMA per 32, in program
+    // order; operand reads are therefore spread between the MFMAs they do not feed (1 MFMA, then
+    // its share of reads, ...) so that their issue time hides under MFMA execution.
+    auto interleave = [&]() { interleave_groups<2 * (C::BN + C::BM), C::BN * C::BM>(); };
+    for (int t = 0; t < steps; ++t) {
+        load_frags(stage_base(t), 16, a1, b1);
+        mma(a0, b0);
+        interleave();
+        __builtin_amdgcn_sched_barrier(0);
+        wait_vmcnt<(C::NSTAGE - 3) * LPS>();
+        __syncthreads();
+        issue(t + C::NSTAGE - 1);
+        load_frags(stage_base(t + 1), 0, a0, b0);
+        mma(a1, b1);
+        interleave();
+        __builtin_amdgcn_sched_barrier(0);
     }
+    wait_vmcnt<0>();                             // trailing zero stages must not land on the epilogue patch
+    __syncthreads();
 
     // Epilogue.  Accumulator register r of block (bn, bm) holds MFMA row 8*(r/4) + 4*(lane/32) + r%4
     // (= m offset) and column lane%32 (= n offset): four adjacent m per register quad.
@@ -213,7 +275,6 @@ load_frags(buf, 0, a0, b0);
         // read-modify-write, against ~4.9 TB/s once every row gets >= 128 contiguous bytes per
         // instruction.  So each 32 x 32 block is turned through a private LDS patch: written as
         // held, read back with 8 lanes per row, then 8 rows x 128 bytes per global access.
-        constexpr int PLD = 36;                            // patch row stride in floats (144 B: conflict-free)
         float* patch = reinterpret_cast<float*>(lds) + wave * (32 * PLD);
         const int prow = lane >> 3, pcol = 4 * (lane & 7);
 #pragma unroll
@@ -281,30 +342,44 @@ psd_status launch_cfg(const uint16_t* U, int64_t ldu, const uint16_t* V, int64_t
     const int64_t tiles_n = (N + C::TN - 1) / C::TN, tiles_m = (M + C::TM - 1) / C::TM;
     const int64_t tiles = tiles_n * tiles_m;
     if (tiles < 1 || tiles > 0x3fffffff) return PSD_E_INVALID;
-    // 32-bit byte offsets into each factor matrix, with room for the two stages of read-ahead
+    // 32-bit byte offsets into each factor matrix, with room for the stages of read-ahead
     const int64_t u_bytes = K * ldu * 2, v_bytes = K * ldv * 2;
-    const int64_t reach = (int64_t(1) << 32) - 8 * KT * (ldu > ldv ? ldu : ldv) * 2 - 4096;
+    const int64_t reach = (int64_t(1) << 32) - (C::NSTAGE + 2) * KT * (ldu > ldv ? ldu : ldv) * 2 - 4096;
     if (u_bytes > reach || v_bytes > reach) return PSD_E_UNSUPPORTED;
     auto kern = sfb_bf16_kernel<C>;
     static bool attr_done = false;    // raising the dynamic LDS limit is idempotent
+    static int first_round = 0;       // workgroups resident at once = compute units x workgroups per CU
     if (!attr_done) {
+        int dev = 0, cus = 0, per_cu = 0;
+        PSD_HIP_TRY(hipGetDevice(&dev));
+        PSD_HIP_TRY(hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev));
         PSD_HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
                                         hipFuncAttributeMaxDynamicSharedMemorySize, int(C::LDS_BYTES)));
+        PSD_HIP_TRY(hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, reinterpret_cast<const void*>(kern),
+                                                                 C::THREADS, C::LDS_BYTES));
+        first_round = cus * per_cu;
         attr_done = true;
     }
+    // one nap = s_sleep 100 = 6400 cycles; a slot's delay = PSD_STAGGER % of the main loop's MFMA cycles
+    const char* se = std::getenv("PSD_STAGGER");
+    const int64_t pct = se ? std::atoi(se) : 0;   // off by default: measured no gain, a lone workgroup only reaches half the MFMA rate
+    const int64_t steps = (K + KT - 1) / KT;
+    const int naps = C::WAVES == 4 ? static_cast<int>(steps * (C::BN * C::BM * 2 * 32) * pct / 100 / 6400) : 0;
     hipLaunchKernelGGL(kern, dim3(static_cast<uint32_t>(tiles)), dim3(C::THREADS), C::LDS_BYTES, st, U, ldu, V, ldv, W,
                        Mom, static_cast<int>(N), static_cast<int>(M), static_cast<int>(K), lr, mu,
                        static_cast<int>(tiles_n), static_cast<int>(tiles_m), static_cast<uint32_t>(u_bytes),
-                       static_cast<uint32_t>(v_bytes));
+                       static_cast<uint32_t>(v_bytes), first_round, naps > 4096 ? 4096 : naps);
     PSD_HIP_TRY(hipGetLastError());
     return PSD_OK;
 }
 
-using Cfg256x256w4 = Cfg<2, 2, 4, 4, 1>;   // 4 wavefronts of 128 x 128, one workgroup per CU
-using Cfg256x128w4 = Cfg<2, 2, 4, 2, 2>;   // 4 wavefronts of 128 x 64, two workgroups per CU
-using Cfg128x256w4 = Cfg<2, 2, 2, 4, 2>;   // 4 wavefronts of 64 x 128, two workgroups per CU
-using Cfg256x256w8 = Cfg<2, 4, 4, 2, 2>;   // 8 wavefronts of 128 x 64, one workgroup per CU
-using Cfg128x128w4 = Cfg<2, 2, 2, 2, 2>;   // small layers: more workgroups
+using Cfg256x256w4 = Cfg<2, 2, 4, 4, 4, 1>;   // 4 wavefronts of 128 x 128, 4 stages (128 KiB), one workgroup per CU
+using Cfg256x128w4 = Cfg<2, 2, 4, 2, 3, 2>;   // 4 wavefronts of 128 x 64, 3 stages (72 KiB), two workgroups per CU
+using Cfg128x256w4 = Cfg<2, 2, 2, 4, 3, 2>;   // 4 wavefronts of 64 x 128, 3 stages (72 KiB), two workgroups per CU
+using Cfg256x256w8 = Cfg<2, 4, 4, 2, 4, 2>;   // 8 wavefronts of 128 x 64, 4 stages (128 KiB), one workgroup per CU
+using Cfg128x128w4 = Cfg<2, 2, 2, 2, 4, 2>;   // small layers: more workgroups (64 KiB, two per CU)
+using Cfg128x128w4s3 = Cfg<2, 2, 2, 2, 3, 3>; // 3 stages (48 KiB), three workgroups per CU
+using Cfg128x64w4s3 = Cfg<2, 2, 2, 1, 3, 4>;  // 128 x 64 tiles, 3 stages (36 KiB), four workgroups per CU
 
 }  // namespace
 
@@ -324,6 +399,8 @@ psd_status launch_sfb_bf16(const uint16_t* U, int64_t ldu, const uint16_t* V, in
         case 2: return launch_cfg<Cfg128x256w4>(U, ldu, V, ldv, W, Mom, N, M, K, lr, mu, st);
         case 3: return launch_cfg<Cfg256x256w8>(U, ldu, V, ldv, W, Mom, N, M, K, lr, mu, st);
         case 4: return launch_cfg<Cfg128x128w4>(U, ldu, V, ldv, W, Mom, N, M, K, lr, mu, st);
+        case 5: return launch_cfg<Cfg128x128w4s3>(U, ldu, V, ldv, W, Mom, N, M, K, lr, mu, st);
+        case 6: return launch_cfg<Cfg128x64w4s3>(U, ldu, V, ldv, W, Mom, N, M, K, lr, mu, st);
         default: return PSD_E_INVALID;
     }
 }
