@@ -32,7 +32,7 @@ PEAK_MFMA_TFLOPS = {"bf16": 2500.0, "f32": 157.3}
 # HBM bytes per launch of the dominant kernel measured with rocprofv3 --pmc (FETCH_SIZE and
 # WRITE_SIZE runs, scaled by a copy kernel of known size); filled in from the committed
 # profile summaries, None where not measured.
-MEASURED_TRAFFIC_BYTES = {"bf16": None, "f32": None}
+MEASURED_TRAFFIC_BYTES = {"bf16": 615_500_000, "f32": None}   # profiles/bench_config5_bf16_hbm_traffic.txt
 
 
 class HipEvents:
@@ -129,6 +129,9 @@ def main():
     ap.add_argument("--rule", choices=["alg3", "vs_dense"], default="alg3")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--extras", default=None, help="also time configs 1-4 and a dense size sweep; write JSON here")
+    ap.add_argument("--copy-probe", type=int, default=0, metavar="MiB",
+                    help="only run a plain device-to-device copy of this many MiB, 10 times (calibrates the "
+                         "FETCH_SIZE / WRITE_SIZE counters: the copy reads and writes exactly that many bytes)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU (peers' factors and gradients are seeded buffers in "
@@ -145,6 +148,15 @@ def main():
     psd.lib()
     dev = "cuda:0"
     torch.cuda.set_device(0)
+    if args.copy_probe:
+        n = args.copy_probe * (1 << 20) // 4
+        src = torch.ones(n, dtype=torch.float32, device=dev)
+        dst = torch.empty_like(src)
+        for _ in range(10):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        print(json.dumps({"copy_probe_MiB": args.copy_probe, "copies": 10}))
+        return 0
     lr, mu = inputs.LR, inputs.MU
     fc_dtype = psd.BF16 if args.fc_dtype == "bf16" else psd.F32
     rule = psd.RULE_ALG3 if args.rule == "alg3" else psd.RULE_SFB_VS_DENSE
