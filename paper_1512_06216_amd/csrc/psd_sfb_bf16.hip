@@ -50,7 +50,7 @@ struct Cfg {
     static constexpr size_t LDS_BYTES =
         size_t(NSTAGE) * STAGE_BYTES > size_t(PATCH_BYTES) ? size_t(NSTAGE) * STAGE_BYTES : size_t(PATCH_BYTES);
     static_assert(A_BYTES % (1024 * WAVES) == 0 && B_BYTES % (1024 * WAVES) == 0, "stage must split into 1 KiB runs");
-    static_assert(RA >= 128 && RB >= 128, "swizzle needs rows of at least 128 bytes");
+    static_assert(RA % 128 == 0 && RB % 128 == 0, "the swizzle permutes chunks inside 128-byte groups");
     static_assert(NSTAGE >= 3, "the pipeline keeps at least one stage in flight beyond the one being awaited");
 };
 
@@ -141,26 +141,29 @@ sfb_bf16_kernel(const uint16_t* __restrict__ U, int64_t ldu, const uint16_t* __r
     const int wn0 = (wave / C::WM) * 32 * C::BN, wm0 = (wave % C::WM) * 32 * C::BM;
     const int grp = lane >> 4, l16 = lane & 15;
 
-    // ---- DMA plan: instruction j of this wavefront moves rows [g*RPI, (g+1)*RPI) of a stage,
-    // lane i carrying the chunk that belongs at physical position i of that 1 KiB run.
+    // ---- DMA plan: instruction j of this wavefront moves one 1 KiB run of a stage (a whole number
+    // of rows, or row fragments for 384-byte rows), lane i carrying the chunk that belongs at
+    // physical position i of that run.
     // physical chunk pc of row r holds logical chunk pc ^ ((r & 3) << 1)
     const i32x4 rsrc_u = factor_rsrc(U, u_bytes), rsrc_v = factor_rsrc(V, v_bytes);
     uint32_t voff_a[C::NI_A], voff_b[C::NI_B];
     {
-        constexpr int LPR = C::RA / 16, RPI = 64 / LPR;
+        constexpr int LPR = C::RA / 16;              // 16-byte chunks per row
 #pragma unroll
         for (int j = 0; j < C::NI_A; ++j) {
-            const int r = (wave * C::NI_A + j) * RPI + lane / LPR;
-            const int lc = (lane % LPR) ^ ((r & 3) << 1);
+            const int f = (wave * C::NI_A + j) * 64 + lane;   // chunk index inside the stage
+            const int r = f / LPR;
+            const int lc = (f % LPR) ^ ((r & 3) << 1);
             voff_a[j] = static_cast<uint32_t>((r * ldu + n0 + lc * 8) * 2);
         }
     }
     {
-        constexpr int LPR = C::RB / 16, RPI = 64 / LPR;
+        constexpr int LPR = C::RB / 16;
 #pragma unroll
         for (int j = 0; j < C::NI_B; ++j) {
-            const int r = (wave * C::NI_B + j) * RPI + lane / LPR;
-            const int lc = (lane % LPR) ^ ((r & 3) << 1);
+            const int f = (wave * C::NI_B + j) * 64 + lane;
+            const int r = f / LPR;
+            const int lc = (f % LPR) ^ ((r & 3) << 1);
             voff_b[j] = static_cast<uint32_t>((r * ldv + m0 + lc * 8) * 2);
         }
     }
@@ -380,18 +383,35 @@ using Cfg256x256w8 = Cfg<2, 4, 4, 2, 4, 2>;   // 8 wavefronts of 128 x 64, 4 sta
 using Cfg128x128w4 = Cfg<2, 2, 2, 2, 4, 2>;   // small layers: more workgroups (64 KiB, two per CU)
 using Cfg128x128w4s3 = Cfg<2, 2, 2, 2, 3, 3>; // 3 stages (48 KiB), three workgroups per CU
 using Cfg128x64w4s3 = Cfg<2, 2, 2, 1, 3, 4>;  // 128 x 64 tiles, 3 stages (36 KiB), four workgroups per CU
+using Cfg128x192w4 = Cfg<2, 2, 2, 3, 4, 2>;   // 4 wavefronts of 64 x 96, 4 stages (80 KiB), two workgroups per CU
+using Cfg128x256w4s3 = Cfg<2, 2, 2, 4, 3, 2>;
+using Cfg128x256w4s6 = Cfg<2, 2, 2, 4, 6, 1>;  // experiments: one workgroup per CU, deep ring
+using Cfg128x256w4s5 = Cfg<2, 2, 2, 4, 5, 1>;
+using Cfg128x256w4s4 = Cfg<2, 2, 2, 4, 4, 1>;
 
 }  // namespace
 
 psd_status launch_sfb_bf16(const uint16_t* U, int64_t ldu, const uint16_t* V, int64_t ldv, float* W, float* Mom,
                            int64_t N, int64_t M, int64_t K, float lr, float mu, hipStream_t st)
 {
-    // PSD_SFB_BF16_TILE overrides the tile choice (tuning aid): 0..4 in the order above
+    // PSD_SFB_BF16_TILE overrides the tile choice (tuning aid): index into the switch below
     const char* e = std::getenv("PSD_SFB_BF16_TILE");
     int pick = e ? std::atoi(e) : -1;
     if (pick < 0) {
-        const int64_t big_tiles = ((N + 255) / 256) * ((M + 255) / 256);
-        pick = big_tiles >= 256 ? 2 : 4;
+        // Workgroups of one launch run in rounds of (CUs x workgroups per CU); a partly filled last
+        // round costs as much as a full one.  Pick the tile whose rounds x tile area is smallest
+        // (ties go to the larger tile; the 128 x 128 tile pays ~10% for its lower MFMA duty).
+        int dev = 0, cus = 256;
+        if (hipGetDevice(&dev) == hipSuccess) (void)hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev);
+        struct Cand { int id, tn, tm, per_cu, weight; };
+        const Cand cands[] = {{2, 128, 256, 2, 100}, {7, 128, 192, 2, 100}, {4, 128, 128, 2, 110}};
+        int64_t best = -1;
+        for (const Cand& c : cands) {
+            const int64_t tiles = ((N + c.tn - 1) / c.tn) * ((M + c.tm - 1) / c.tm);
+            const int64_t slots = int64_t(cus) * c.per_cu;
+            const int64_t cost = ((tiles + slots - 1) / slots) * c.tn * c.tm * c.weight;
+            if (best < 0 || cost < best) { best = cost; pick = c.id; }
+        }
     }
     switch (pick) {
         case 0: return launch_cfg<Cfg256x256w4>(U, ldu, V, ldv, W, Mom, N, M, K, lr, mu, st);
@@ -401,6 +421,10 @@ psd_status launch_sfb_bf16(const uint16_t* U, int64_t ldu, const uint16_t* V, in
         case 4: return launch_cfg<Cfg128x128w4>(U, ldu, V, ldv, W, Mom, N, M, K, lr, mu, st);
         case 5: return launch_cfg<Cfg128x128w4s3>(U, ldu, V, ldv, W, Mom, N, M, K, lr, mu, st);
         case 6: return launch_cfg<Cfg128x64w4s3>(U, ldu, V, ldv, W, Mom, N, M, K, lr, mu, st);
+        case 7: return launch_cfg<Cfg128x192w4>(U, ldu, V, ldv, W, Mom, N, M, K, lr, mu, st);
+        case 8: return launch_cfg<Cfg128x256w4s6>(U, ldu, V, ldv, W, Mom, N, M, K, lr, mu, st);
+        case 9: return launch_cfg<Cfg128x256w4s5>(U, ldu, V, ldv, W, Mom, N, M, K, lr, mu, st);
+        case 10: return launch_cfg<Cfg128x256w4s4>(U, ldu, V, ldv, W, Mom, N, M, K, lr, mu, st);
         default: return PSD_E_INVALID;
     }
 }
