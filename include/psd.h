@@ -109,8 +109,8 @@ psd_status psd_sync_fc_sfb(const psd_plan* plan, int32_t factor_dtype,
  * momentum update on W[i], Mom[i].
  *   G [host] array of P [dev] pointers to n fp32 each (read only); W, Mom [dev] n fp32,
  *   in place.  1 <= P <= PSD_MAX_WORKERS; n >= 0 (n == 0 is a no-op); 1 <= S <= n.
- * Shard s (psd_shard_range) is processed by the workgroups with blockIdx % S == s, which
- * for S = 8 places one shard on each of the chip's 8 XCDs. */
+ * The shards (psd_shard_range) are processed one after the other in key order inside one
+ * launch; S changes which workgroup touches which key, never a value. */
 psd_status psd_sync_dense_ps(int64_t n, int32_t P, const float* const* G,
                              float* W, float* Mom, float lr, float mu, int32_t S, void* stream);
 

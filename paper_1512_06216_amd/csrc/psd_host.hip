@@ -168,6 +168,7 @@ psd_status psd_sync_dense_ps(int64_t n, int32_t P, const float* const* G, float*
     DenseWide a;
     for (int p = 0; p < PSD_MAX_WORKERS; ++p) a.G[p] = p < P ? G[p] : nullptr;
     a.W = W; a.Mom = Mom; a.n = n; a.P = P; a.S = S;
+    a.q = n / S; a.r = n % S;
     a.chunks = dense_chunks_for(n, S);
     return launch_dense_wide(a, lr, mu, static_cast<hipStream_t>(stream));
 }
@@ -187,6 +188,7 @@ psd_status psd_sync_dense_ps_multi(int32_t L, const psd_dense_segment* segs, flo
         DenseSeg& d = t.seg[used++];
         for (int p = 0; p < PSD_MAX_MULTI_WORKERS; ++p) d.G[p] = p < s.P ? s.G[p] : nullptr;
         d.W = s.W; d.Mom = s.Mom; d.n = s.n; d.P = s.P; d.S = s.S;
+        d.q = s.n / s.S; d.r = s.n % s.S;
         d.chunks = dense_chunks_for(s.n, s.S);
         d.block_begin = static_cast<int32_t>(blocks);
         blocks += static_cast<int64_t>(d.chunks) * s.S;

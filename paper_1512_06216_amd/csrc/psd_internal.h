@@ -23,6 +23,7 @@ struct DenseSeg {
     float* W;
     float* Mom;
     int64_t n;
+    int64_t q, r;          // n = q * S + r, 0 <= r < S
     int32_t P;
     int32_t S;
     int32_t block_begin;   // first workgroup of this segment
@@ -37,6 +38,7 @@ struct DenseWide {          // single layer, up to PSD_MAX_WORKERS copies
     float* W;
     float* Mom;
     int64_t n;
+    int64_t q, r;          // n = q * S + r, 0 <= r < S
     int32_t P;
     int32_t S;
     int32_t chunks;

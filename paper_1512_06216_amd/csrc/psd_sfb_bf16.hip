@@ -109,18 +109,9 @@ template <class C>
 __global__ void __launch_bounds__(C::THREADS, C::OCC)
 sfb_bf16_kernel(const uint16_t* __restrict__ U, int64_t ldu, const uint16_t* __restrict__ V, int64_t ldv,
                 float* __restrict__ W, float* __restrict__ Mom, int N, int M, int K, float lr, float mu,
-                int tiles_n, int tiles_m, uint32_t u_bytes, uint32_t v_bytes, int first_round, int stagger_naps)
+                int tiles_n, int tiles_m, uint32_t u_bytes, uint32_t v_bytes)
 {
     extern __shared__ __attribute__((aligned(1024))) uint16_t lds[];
-    // Workgroups that start together run in lock step: all in the MFMA loop (HBM idle), then all in
-    // the W/Mom epilogue (MFMA idle).  The workgroups of the first round that sit in the second,
-    // third... wave slot of their SIMDs therefore start late by about one main loop, so that from
-    // then on one resident workgroup's epilogue overlaps the other's main loop.  A sleeping
-    // workgroup costs nothing: its neighbour gets the whole MFMA pipe meanwhile.
-    if (static_cast<int>(blockIdx.x) < first_round) {
-        const unsigned slot = __builtin_amdgcn_s_getreg((3 << 11) | 4);   // HW_ID bits [3:0]: wave slot in its SIMD
-        for (unsigned i = 0; i < slot * static_cast<unsigned>(stagger_naps); ++i) __builtin_amdgcn_s_sleep(100);
-    }
     const uint32_t lds0 = static_cast<uint32_t>(reinterpret_cast<uintptr_t>(
         (__attribute__((address_space(3))) void*)lds));
 
@@ -351,27 +342,15 @@ psd_status launch_cfg(const uint16_t* U, int64_t ldu, const uint16_t* V, int64_t
     if (u_bytes > reach || v_bytes > reach) return PSD_E_UNSUPPORTED;
     auto kern = sfb_bf16_kernel<C>;
     static bool attr_done = false;    // raising the dynamic LDS limit is idempotent
-    static int first_round = 0;       // workgroups resident at once = compute units x workgroups per CU
     if (!attr_done) {
-        int dev = 0, cus = 0, per_cu = 0;
-        PSD_HIP_TRY(hipGetDevice(&dev));
-        PSD_HIP_TRY(hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev));
         PSD_HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
                                         hipFuncAttributeMaxDynamicSharedMemorySize, int(C::LDS_BYTES)));
-        PSD_HIP_TRY(hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, reinterpret_cast<const void*>(kern),
-                                                                 C::THREADS, C::LDS_BYTES));
-        first_round = cus * per_cu;
         attr_done = true;
     }
-    // one nap = s_sleep 100 = 6400 cycles; a slot's delay = PSD_STAGGER % of the main loop's MFMA cycles
-    const char* se = std::getenv("PSD_STAGGER");
-    const int64_t pct = se ? std::atoi(se) : 0;   // off by default: measured no gain, a lone workgroup only reaches half the MFMA rate
-    const int64_t steps = (K + KT - 1) / KT;
-    const int naps = C::WAVES == 4 ? static_cast<int>(steps * (C::BN * C::BM * 2 * 32) * pct / 100 / 6400) : 0;
     hipLaunchKernelGGL(kern, dim3(static_cast<uint32_t>(tiles)), dim3(C::THREADS), C::LDS_BYTES, st, U, ldu, V, ldv, W,
                        Mom, static_cast<int>(N), static_cast<int>(M), static_cast<int>(K), lr, mu,
                        static_cast<int>(tiles_n), static_cast<int>(tiles_m), static_cast<uint32_t>(u_bytes),
-                       static_cast<uint32_t>(v_bytes), first_round, naps > 4096 ? 4096 : naps);
+                       static_cast<uint32_t>(v_bytes));
     PSD_HIP_TRY(hipGetLastError());
     return PSD_OK;
 }
@@ -384,10 +363,6 @@ using Cfg128x128w4 = Cfg<2, 2, 2, 2, 4, 2>;   // small layers: more workgroups (
 using Cfg128x128w4s3 = Cfg<2, 2, 2, 2, 3, 3>; // 3 stages (48 KiB), three workgroups per CU
 using Cfg128x64w4s3 = Cfg<2, 2, 2, 1, 3, 4>;  // 128 x 64 tiles, 3 stages (36 KiB), four workgroups per CU
 using Cfg128x192w4 = Cfg<2, 2, 2, 3, 4, 2>;   // 4 wavefronts of 64 x 96, 4 stages (80 KiB), two workgroups per CU
-using Cfg128x256w4s3 = Cfg<2, 2, 2, 4, 3, 2>;
-using Cfg128x256w4s6 = Cfg<2, 2, 2, 4, 6, 1>;  // experiments: one workgroup per CU, deep ring
-using Cfg128x256w4s5 = Cfg<2, 2, 2, 4, 5, 1>;
-using Cfg128x256w4s4 = Cfg<2, 2, 2, 4, 4, 1>;
 
 }  // namespace
 
@@ -422,9 +397,6 @@ psd_status launch_sfb_bf16(const uint16_t* U, int64_t ldu, const uint16_t* V, in
         case 5: return launch_cfg<Cfg128x128w4s3>(U, ldu, V, ldv, W, Mom, N, M, K, lr, mu, st);
         case 6: return launch_cfg<Cfg128x64w4s3>(U, ldu, V, ldv, W, Mom, N, M, K, lr, mu, st);
         case 7: return launch_cfg<Cfg128x192w4>(U, ldu, V, ldv, W, Mom, N, M, K, lr, mu, st);
-        case 8: return launch_cfg<Cfg128x256w4s6>(U, ldu, V, ldv, W, Mom, N, M, K, lr, mu, st);
-        case 9: return launch_cfg<Cfg128x256w4s5>(U, ldu, V, ldv, W, Mom, N, M, K, lr, mu, st);
-        case 10: return launch_cfg<Cfg128x256w4s4>(U, ldu, V, ldv, W, Mom, N, M, K, lr, mu, st);
         default: return PSD_E_INVALID;
     }
 }

@@ -6,11 +6,18 @@
 // (v_mfma_f32_32x32x2_f32: one k per lane, which is exactly how the K-outer stacked
 // factors sit in memory -- no transpose is needed for fp32).
 //
-// Tiling: a 256-lane workgroup (4 wavefronts, 2 x 2) owns a 128 x 128 tile of W; each
-// wavefront a 64 x 64 sub-tile as 2 x 2 MFMA blocks of 32 x 32.  MFMA row i of block t
+// Tiling: a 256-lane workgroup (4 wavefronts, 2 x 2) owns a 128 x 128 (or 64 x 128) tile of W;
+// each wavefront a 64 x 64 (32 x 64) sub-tile of 32 x 32 MFMA blocks.  MFMA row i of block t
 // stands for n = n0 + 2*i + t (columns likewise), so one lane's LDS operand read is one
 // 8-byte load and one lane owns 2 adjacent m in the epilogue (8-byte W/Mom accesses,
 // 256 contiguous bytes per half wavefront).  dW lives only in accumulator registers.
+//
+// Feeding: the same scheme as the bf16 kernel.  Tiles go global -> LDS without registers
+// (buffer_load_dwordx4 ... lds) into a ring of NSTAGE buffers with NSTAGE-1 stages in flight;
+// the buffer range check zero-fills the K tail.  A stage is 16 k rows = two half-stages of
+// 4 MFMA k-pairs; the operand reads of one half are issued before the MFMAs of the half before
+// and interleaved with them, and the workgroup barrier sits between the two halves.
+#include <cstdlib>
 #include "psd_internal.h"
 
 namespace psd {
@@ -18,118 +25,222 @@ namespace {
 
 typedef float f32x16 __attribute__((ext_vector_type(16)));
 
-constexpr int TN = 128, TM = 128;   // workgroup tile (n, m)
+typedef int i32x4 __attribute__((ext_vector_type(4)));
+typedef float f32x2 __attribute__((ext_vector_type(2)));
+
+constexpr int TM = 128;             // workgroup tile width (m)
 constexpr int KT = 16;              // k rows per LDS stage
 constexpr int THREADS = 256;
+constexpr int NSTAGE = 4;           // ring depth
 
-// Loads one 16-byte chunk of a K-outer operand row, or zeros outside the matrix.
-__device__ __forceinline__ float4 ld_chunk(const float* __restrict__ X, int64_t ld, int64_t k, int64_t K, int64_t col)
+__device__ __forceinline__ void upd(float d, float& w, float& mo, float lr, float mu)
 {
-    if (k < K && col < ld) return *reinterpret_cast<const float4*>(X + k * ld + col);   // ld % 4 == 0
-    return make_float4(0.f, 0.f, 0.f, 0.f);
+    mo = __fmaf_rn(mu, mo, lr * d);
+    w = w - mo;
 }
 
+// global -> LDS, 16 bytes per lane: lane i's chunk lands at lds_addr + 16*i; a lane whose
+// offset is at or past the descriptor's size writes zeros
+__device__ __forceinline__ void dma_b128(uint32_t lds_addr_uniform, uint32_t voff, i32x4 rsrc)
+{
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tbuffer_load_dwordx4 %1, %2, 0 offen lds"
+                 :
+                 : "s"(lds_addr_uniform), "v"(voff), "s"(rsrc)
+                 : "memory");
+}
+
+template <int N>
+__device__ __forceinline__ void wait_vmcnt()
+{
+    asm volatile("s_waitcnt vmcnt(%0)" : : "n"(N) : "memory");
+}
+
+__device__ __forceinline__ i32x4 factor_rsrc(const float* X, uint32_t bytes)
+{
+    const uint64_t a = reinterpret_cast<uint64_t>(X);
+    i32x4 r;
+    r.x = static_cast<int>(a & 0xffffffffu);
+    r.y = static_cast<int>((a >> 32) & 0xffffu);      // stride 0: raw buffer, byte-granular range check
+    r.z = static_cast<int>(bytes);
+    r.w = 0x00020000;
+    return r;
+}
+
+// 1 MFMA, then its share of the LDS reads of the next half-stage, and so on
+template <int R, int MF, int I = 0>
+__device__ __forceinline__ void interleave_groups()
+{
+    if constexpr (I < MF) {
+        __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+        constexpr int n = R * (I + 1) / MF - R * I / MF;
+        if constexpr (n > 0) __builtin_amdgcn_sched_group_barrier(0x100, n, 0);
+        interleave_groups<R, MF, I + 1>();
+    }
+}
+
+// BN = MFMA blocks per wavefront along n: workgroup tile (64*BN) x 128, wavefront tile (32*BN) x 64.
+// BN = 2 is the default; BN = 1 doubles the number of workgroups for layers with few tiles.
+template <int BN>
 __global__ void __launch_bounds__(THREADS)
 sfb_f32_kernel(const float* __restrict__ U, int64_t ldu, const float* __restrict__ V, int64_t ldv,
                float* __restrict__ W, float* __restrict__ Mom, int N, int M, int K, float lr, float mu,
-               int tiles_m)
+               int tiles_m, uint32_t u_bytes, uint32_t v_bytes)
 {
-    __shared__ __attribute__((aligned(16))) float As[2][KT][TN];
-    __shared__ __attribute__((aligned(16))) float Bs[2][KT][TM];
+    constexpr int TN = 64 * BN;
+    constexpr int RA = TN * 4, RB = TM * 4;                       // LDS row bytes
+    constexpr int A_BYTES = KT * RA, B_BYTES = KT * RB, STAGE_BYTES = A_BYTES + B_BYTES;
+    constexpr int NI_A = A_BYTES / 1024 / 4, NI_B = B_BYTES / 1024 / 4;   // 1 KiB DMA runs per wavefront
+    constexpr int LPS = NI_A + NI_B;
+    __shared__ __attribute__((aligned(1024))) char lds[NSTAGE * STAGE_BYTES];
+    const uint32_t lds0 = static_cast<uint32_t>(reinterpret_cast<uintptr_t>(
+        (__attribute__((address_space(3))) void*)lds));
 
     const int tile_n = blockIdx.x / tiles_m, tile_m = blockIdx.x % tiles_m;
     const int64_t n0 = int64_t(tile_n) * TN, m0 = int64_t(tile_m) * TM;
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const int wn0 = (wave >> 1) * 64, wm0 = (wave & 1) * 64;     // wavefront sub-tile origin
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int wn0 = (wave >> 1) * 32 * BN, wm0 = (wave & 1) * 64;     // wavefront sub-tile origin
     const int l32 = lane & 31, lhi = lane >> 5;
 
-    // global -> LDS assignment: a stage is KT rows x 32 chunks per operand = 512 chunks, 2 per lane
-    const int ld_row = tid >> 5;          // 0..7 (and +8)
-    const int ld_col = (tid & 31) * 4;    // float offset inside the tile row
-
-    f32x16 acc[2][2];
+    // DMA plan: run j of this wavefront covers chunks f = (wave*NI + j)*64 + lane of the stage
+    const i32x4 rsrc_u = factor_rsrc(U, u_bytes), rsrc_v = factor_rsrc(V, v_bytes);
+    uint32_t voff_a[NI_A], voff_b[NI_B];
 #pragma unroll
-    for (int a = 0; a < 2; ++a)
+    for (int j = 0; j < NI_A; ++j) {
+        const int f = (wave * NI_A + j) * 64 + lane;
+        voff_a[j] = static_cast<uint32_t>(((f / (TN / 4)) * ldu + n0 + (f % (TN / 4)) * 4) * 4);
+    }
+#pragma unroll
+    for (int j = 0; j < NI_B; ++j) {
+        const int f = (wave * NI_B + j) * 64 + lane;
+        voff_b[j] = static_cast<uint32_t>(((f / (TM / 4)) * ldv + m0 + (f % (TM / 4)) * 4) * 4);
+    }
+    const uint32_t step_a = static_cast<uint32_t>(KT * ldu * 4), step_b = static_cast<uint32_t>(KT * ldv * 4);
+    auto issue = [&](int t) {                    // stage t -> ring buffer t % NSTAGE; past K: zeros
+        const uint32_t base = lds0 + static_cast<uint32_t>(t % NSTAGE) * STAGE_BYTES;
+#pragma unroll
+        for (int j = 0; j < NI_A; ++j)
+            dma_b128(base + (wave * NI_A + j) * 1024, voff_a[j] + static_cast<uint32_t>(t) * step_a, rsrc_u);
+#pragma unroll
+        for (int j = 0; j < NI_B; ++j)
+            dma_b128(base + A_BYTES + (wave * NI_B + j) * 1024, voff_b[j] + static_cast<uint32_t>(t) * step_b, rsrc_v);
+    };
+
+    f32x16 acc[BN][2];
+#pragma unroll
+    for (int a = 0; a < BN; ++a)
 #pragma unroll
         for (int b = 0; b < 2; ++b)
 #pragma unroll
             for (int r = 0; r < 16; ++r) acc[a][b][r] = 0.f;
 
-    float4 ra[2], rb[2];
-    auto fetch = [&](int64_t k0) {
+    // One half-stage = 4 MFMA k-pairs.  Lanes 0..31 feed k = 2*kk, lanes 32..63 feed k = 2*kk + 1.
+    // MFMA row i of block t stands for n = 2*i + t (BN = 2) or n = i (BN = 1); columns m = 2*j + t.
+    struct Half { f32x2 a[4]; f32x2 b[4]; };
+    const uint32_t rd_a = static_cast<uint32_t>(lhi * RA + (wn0 + BN * l32) * 4);
+    const uint32_t rd_b = static_cast<uint32_t>(A_BYTES + lhi * RB + (wm0 + 2 * l32) * 4);
+    auto load_half = [&](int t, int h, Half& f) {
+        const uint32_t base = lds0 + static_cast<uint32_t>(t % NSTAGE) * STAGE_BYTES;
 #pragma unroll
-        for (int h = 0; h < 2; ++h) {
-            ra[h] = ld_chunk(U, ldu, k0 + ld_row + 8 * h, K, n0 + ld_col);
-            rb[h] = ld_chunk(V, ldv, k0 + ld_row + 8 * h, K, m0 + ld_col);
+        for (int kk = 0; kk < 4; ++kk) {
+            const int krow = 2 * (4 * h + kk);
+            const auto pa = reinterpret_cast<__attribute__((address_space(3))) const char*>(base + rd_a + krow * RA);
+            const auto pb = reinterpret_cast<__attribute__((address_space(3))) const char*>(base + rd_b + krow * RB);
+            if constexpr (BN == 2) f.a[kk] = *reinterpret_cast<__attribute__((address_space(3))) const f32x2*>(pa);
+            else f.a[kk].x = *reinterpret_cast<__attribute__((address_space(3))) const float*>(pa);
+            f.b[kk] = *reinterpret_cast<__attribute__((address_space(3))) const f32x2*>(pb);
         }
     };
-    auto stash = [&](int buf) {
+    auto mma_half = [&](const Half& f) {
 #pragma unroll
-        for (int h = 0; h < 2; ++h) {
-            *reinterpret_cast<float4*>(&As[buf][ld_row + 8 * h][ld_col]) = ra[h];
-            *reinterpret_cast<float4*>(&Bs[buf][ld_row + 8 * h][ld_col]) = rb[h];
+        for (int kk = 0; kk < 4; ++kk) {
+            acc[0][0] = __builtin_amdgcn_mfma_f32_32x32x2f32(f.a[kk].x, f.b[kk].x, acc[0][0], 0, 0, 0);
+            acc[0][1] = __builtin_amdgcn_mfma_f32_32x32x2f32(f.a[kk].x, f.b[kk].y, acc[0][1], 0, 0, 0);
+            if constexpr (BN == 2) {
+                acc[1][0] = __builtin_amdgcn_mfma_f32_32x32x2f32(f.a[kk].y, f.b[kk].x, acc[1][0], 0, 0, 0);
+                acc[1][1] = __builtin_amdgcn_mfma_f32_32x32x2f32(f.a[kk].y, f.b[kk].y, acc[1][1], 0, 0, 0);
+            }
         }
     };
+    auto interleave = [&]() { interleave_groups<8, 8 * BN>(); };
 
     const int steps = (K + KT - 1) / KT;
-    fetch(0);
-    stash(0);
-    __syncthreads();
-    for (int s = 0; s < steps; ++s) {
-        const int buf = s & 1;
-        if (s + 1 < steps) fetch(int64_t(s + 1) * KT);
 #pragma unroll
-        for (int kk = 0; kk < KT; kk += 2) {
-            // lanes 0..31 feed k = kk, lanes 32..63 feed k = kk + 1
-            const float2 a = *reinterpret_cast<const float2*>(&As[buf][kk + lhi][wn0 + 2 * l32]);
-            const float2 b = *reinterpret_cast<const float2*>(&Bs[buf][kk + lhi][wm0 + 2 * l32]);
-            acc[0][0] = __builtin_amdgcn_mfma_f32_32x32x2f32(a.x, b.x, acc[0][0], 0, 0, 0);
-            acc[0][1] = __builtin_amdgcn_mfma_f32_32x32x2f32(a.x, b.y, acc[0][1], 0, 0, 0);
-            acc[1][0] = __builtin_amdgcn_mfma_f32_32x32x2f32(a.y, b.x, acc[1][0], 0, 0, 0);
-            acc[1][1] = __builtin_amdgcn_mfma_f32_32x32x2f32(a.y, b.y, acc[1][1], 0, 0, 0);
-        }
-        if (s + 1 < steps) {
-            stash(buf ^ 1);          // the other buffer was last read before the previous barrier
-            __syncthreads();
-        }
+    for (int t = 0; t < NSTAGE - 1; ++t) issue(t);
+    wait_vmcnt<(NSTAGE - 2) * LPS>();
+    __syncthreads();
+    Half h0, h1;
+    load_half(0, 0, h0);
+    for (int t = 0; t < steps; ++t) {
+        load_half(t, 1, h1);
+        mma_half(h0);
+        interleave();
+        __builtin_amdgcn_sched_barrier(0);
+        wait_vmcnt<(NSTAGE - 3) * LPS>();         // stage t+1 has landed
+        __syncthreads();                          // ... for every wavefront, and stage t-1 is free
+        issue(t + NSTAGE - 1);
+        load_half(t + 1, 0, h0);
+        mma_half(h1);
+        interleave();
+        __builtin_amdgcn_sched_barrier(0);
     }
+    wait_vmcnt<0>();                              // nothing may still be landing in LDS at exit
 
     // Epilogue.  Accumulator register r of a 32x32 block holds MFMA row 8*(r/4) + 4*(lane/32) + r%4,
-    // column lane%32.  Block (ta, tb): n = n0 + wn0 + 2*row + ta, m = m0 + wm0 + 2*col + tb.
+    // column lane%32.  Block (ta, tb): n = n0 + wn0 + BN*row + ta, m = m0 + wm0 + 2*col + tb.
     const int64_t mcol = m0 + wm0 + 2 * l32;
     const bool pair_ok = (M % 2 == 0);   // 8-byte accesses need an even row length
 #pragma unroll
-    for (int ta = 0; ta < 2; ++ta) {
+    for (int ta = 0; ta < BN; ++ta) {
 #pragma unroll
         for (int r = 0; r < 16; ++r) {
             const int row = 8 * (r >> 2) + 4 * lhi + (r & 3);
-            const int64_t n = n0 + wn0 + 2 * row + ta;
+            const int64_t n = n0 + wn0 + BN * row + ta;
             if (n >= N) continue;
             const float d0 = acc[ta][0][r], d1 = acc[ta][1][r];
             float* wp = W + n * int64_t(M) + mcol;
             float* mp = Mom + n * int64_t(M) + mcol;
             if (pair_ok && mcol + 1 < M) {
                 float2 w = *reinterpret_cast<float2*>(wp), mo = *reinterpret_cast<float2*>(mp);
-                mo.x = __fmaf_rn(mu, mo.x, lr * d0);
-                mo.y = __fmaf_rn(mu, mo.y, lr * d1);
-                w.x -= mo.x;
-                w.y -= mo.y;
+                upd(d0, w.x, mo.x, lr, mu);
+                upd(d1, w.y, mo.y, lr, mu);
                 *reinterpret_cast<float2*>(mp) = mo;
                 *reinterpret_cast<float2*>(wp) = w;
             } else {
                 if (mcol < M) {
-                    const float mo = __fmaf_rn(mu, mp[0], lr * d0);
+                    float w = wp[0], mo = mp[0];
+                    upd(d0, w, mo, lr, mu);
                     mp[0] = mo;
-                    wp[0] -= mo;
+                    wp[0] = w;
                 }
                 if (mcol + 1 < M) {
-                    const float mo = __fmaf_rn(mu, mp[1], lr * d1);
+                    float w = wp[1], mo = mp[1];
+                    upd(d1, w, mo, lr, mu);
                     mp[1] = mo;
-                    wp[1] -= mo;
+                    wp[1] = w;
                 }
             }
         }
     }
+}
+
+template <int BN>
+psd_status launch_f32(const float* U, int64_t ldu, const float* V, int64_t ldv, float* W, float* Mom,
+                      int64_t N, int64_t M, int64_t K, float lr, float mu, hipStream_t st)
+{
+    constexpr int TN = 64 * BN;
+    const int64_t tiles_n = (N + TN - 1) / TN, tiles_m = (M + TM - 1) / TM;
+    const int64_t tiles = tiles_n * tiles_m;
+    if (tiles < 1 || tiles > 0x7fffffff) return PSD_E_INVALID;
+    // 32-bit byte offsets into each factor matrix, with room for the stages of read-ahead
+    const int64_t u_bytes = K * ldu * 4, v_bytes = K * ldv * 4;
+    const int64_t reach = (int64_t(1) << 32) - (NSTAGE + 2) * KT * (ldu > ldv ? ldu : ldv) * 4 - 4096;
+    if (u_bytes > reach || v_bytes > reach) return PSD_E_UNSUPPORTED;
+    hipLaunchKernelGGL(sfb_f32_kernel<BN>, dim3(static_cast<uint32_t>(tiles)), dim3(THREADS), 0, st, U, ldu, V, ldv, W,
+                       Mom, static_cast<int>(N), static_cast<int>(M), static_cast<int>(K), lr, mu,
+                       static_cast<int>(tiles_m), static_cast<uint32_t>(u_bytes), static_cast<uint32_t>(v_bytes));
+    PSD_HIP_TRY(hipGetLastError());
+    return PSD_OK;
 }
 
 }  // namespace
@@ -137,14 +248,15 @@ sfb_f32_kernel(const float* __restrict__ U, int64_t ldu, const float* __restrict
 psd_status launch_sfb_f32(const float* U, int64_t ldu, const float* V, int64_t ldv, float* W, float* Mom,
                           int64_t N, int64_t M, int64_t K, float lr, float mu, hipStream_t st)
 {
-    const int64_t tiles_n = (N + TN - 1) / TN, tiles_m = (M + TM - 1) / TM;
-    const int64_t tiles = tiles_n * tiles_m;
-    if (tiles < 1 || tiles > 0x7fffffff) return PSD_E_INVALID;
-    hipLaunchKernelGGL(sfb_f32_kernel, dim3(static_cast<uint32_t>(tiles)), dim3(THREADS), 0, st, U, ldu, V, ldv, W, Mom,
-                       static_cast<int>(N), static_cast<int>(M), static_cast<int>(K), lr, mu,
-                       static_cast<int>(tiles_m));
-    PSD_HIP_TRY(hipGetLastError());
-    return PSD_OK;
+    // 128 x 128 tiles unless that leaves fewer than two workgroups per compute unit (one workgroup's
+    // four wavefronts cannot hide LDS and barrier latency on their own)
+    int dev = 0, cus = 256;
+    if (hipGetDevice(&dev) == hipSuccess) (void)hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev);
+    const int64_t tiles128 = ((N + 127) / 128) * ((M + TM - 1) / TM);
+    const char* e = std::getenv("PSD_SFB_F32_TILE");   // tuning aid: 1 or 2
+    const int bn = e ? std::atoi(e) : (tiles128 < 2 * int64_t(cus) ? 1 : 2);
+    if (bn == 1) return launch_f32<1>(U, ldu, V, ldv, W, Mom, N, M, K, lr, mu, st);
+    return launch_f32<2>(U, ldu, V, ldv, W, Mom, N, M, K, lr, mu, st);
 }
 
 }  // namespace psd
