@@ -32,7 +32,7 @@ PEAK_MFMA_TFLOPS = {"bf16": 2500.0, "f32": 157.3}
 # HBM bytes per launch of the dominant kernel measured with rocprofv3 --pmc (FETCH_SIZE and
 # WRITE_SIZE runs, scaled by a copy kernel of known size); filled in from the committed
 # profile summaries, None where not measured.
-MEASURED_TRAFFIC_BYTES = {"bf16": 615_500_000, "f32": None}   # profiles/bench_config5_bf16_hbm_traffic.txt
+MEASURED_TRAFFIC_BYTES = {"bf16": 923_700_000, "f32": None}   # fc6 launch; profiles/bench_config5_bf16_hbm_traffic.txt
 
 
 class HipEvents:
@@ -67,12 +67,14 @@ class HipEvents:
         self.all = []
 
 
-def build_device_sets(layers, fc_dtype, n_sets, psd, torch, dev):
+def build_device_sets(layers, fc_dtype, n_sets, psd, torch, dev, one_stream=False):
     """Uploads `n_sets` independent copies of every layer's buffers (rotated between steps so
     that a step never finds its operands in the 256 MB last-level cache from the step before)."""
     sets = []
     for _ in range(n_sets):
         streams = [torch.cuda.Stream(device=dev) for _ in layers]
+        if one_stream:
+            streams = [streams[0]] * len(layers)
         tasks = []
         for L, st in zip(layers, streams):
             if L["kind"] == "conv":
@@ -127,6 +129,8 @@ def main():
     ap.add_argument("--fc-dtype", choices=["bf16", "f32"], default="bf16")
     ap.add_argument("--sets", type=int, default=2, help="rotating buffer sets")
     ap.add_argument("--rule", choices=["alg3", "vs_dense"], default="alg3")
+    ap.add_argument("--one-stream", action="store_true",
+                    help="put every layer on the same stream (comparison only; the path uses one stream per layer)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--extras", default=None, help="also time configs 1-4 and a dense size sweep; write JSON here")
     ap.add_argument("--copy-probe", type=int, default=0, metavar="MiB",
@@ -165,7 +169,7 @@ def main():
     for L in layers:
         L["S"] = inputs.CNN_S
         L.setdefault("B", inputs.CNN_B)
-    sets = build_device_sets(layers, fc_dtype, args.sets, psd, torch, dev)
+    sets = build_device_sets(layers, fc_dtype, args.sets, psd, torch, dev, args.one_stream)
     work = [layer_work(L, args.fc_dtype) for L in layers]
     torch.cuda.synchronize()
 
@@ -220,9 +224,9 @@ def main():
     fc_flops = sum(work[j]["flops"] for j in fc_idx)
     value = fc_flops / (ms_per_step * 1e-3) / 1e12
 
-    # dominant kernel: the large-tile reconstruct+update kernel, launched for fc6 and fc7 in every
-    # step; per-launch figures are means over both launches (as a per-kernel profile reports them)
-    dom = [j for j in fc_idx if layers[j]["name"] in ("fc6", "fc7")]
+    # dominant kernel: the bf16/fp32 reconstruct+update kernel of the largest layer (fc6); it has a
+    # kernel instantiation of its own, so a per-kernel profile reports exactly these launches
+    dom = [j for j in fc_idx if layers[j]["name"] == "fc6"]
     dom_bytes = float(np.mean([work[j]["bytes"] for j in dom]))
     dom_flops = float(np.mean([work[j]["flops"] for j in dom]))
     dom_ms = float(np.mean([mean_ms[j] for j in dom]))
@@ -236,7 +240,7 @@ def main():
     else:
         roofline = dict(bound="mfma", achieved=round(mfma_tf, 2), peak=peak_tf, unit="TFLOP/s",
                         frac=round(mfma_tf / peak_tf, 4), traffic=MEASURED_TRAFFIC_BYTES["f32"])
-    roofline.update(kernel="sfb_%s_kernel (fc6, fc7 launches)" % args.fc_dtype,
+    roofline.update(kernel="sfb_%s_kernel, fc6 launches (9216 -> 4096, K = 2048)" % args.fc_dtype,
                     avg_launch_ms=round(dom_ms, 5), algorithmic_bytes_per_launch=int(dom_bytes),
                     flops_per_launch=int(dom_flops), mfma_tflops=round(mfma_tf, 2),
                     mfma_frac=round(mfma_tf / peak_tf, 4), hbm_gbps=round(hbm_gbs, 1),
@@ -252,7 +256,7 @@ def main():
         "config": {"workload": "config5_full_8layer_cnn_iteration", "fc_factor_dtype": args.fc_dtype,
                    "accumulate": "f32", "B": inputs.CNN_B, "P": inputs.CNN_P, "S": inputs.CNN_S,
                    "conv_keys": inputs.conv_sizes(), "fc_shapes_MxN": inputs.FC_SHAPES,
-                   "rule": args.rule, "rotating_sets": args.sets, "streams": len(layers),
+                   "rule": args.rule, "rotating_sets": args.sets, "streams": 1 if args.one_stream else len(layers),
                    "fc_flops_per_step": fc_flops},
         "roofline": roofline,
         "dense_shard_sum": {"GBps_sum_of_kernels": round(conv_bytes / conv_ms / 1e6, 1),
