@@ -19,6 +19,7 @@
 // MFMA operand roles are swapped (rows = m, columns = n) so that the four consecutive
 // accumulator rows a lane owns are four adjacent m of one W row; the epilogue turns each
 // block through LDS so that W and Mom move in 16-byte accesses, 128 contiguous bytes per row.
+#include <atomic>
 #include <cstdlib>
 #include "psd_internal.h"
 
@@ -341,11 +342,13 @@ psd_status launch_cfg(const uint16_t* U, int64_t ldu, const uint16_t* V, int64_t
     const int64_t reach = (int64_t(1) << 32) - (C::NSTAGE + 2) * KT * (ldu > ldv ? ldu : ldv) * 2 - 4096;
     if (u_bytes > reach || v_bytes > reach) return PSD_E_UNSUPPORTED;
     auto kern = sfb_bf16_kernel<C>;
-    static bool attr_done = false;    // raising the dynamic LDS limit is idempotent
-    if (!attr_done) {
+    // raise the dynamic LDS limit once per process (idempotent, so a race between two first
+    // callers is harmless; the flag only saves the call on later launches)
+    static std::atomic<bool> attr_done{false};
+    if (!attr_done.load(std::memory_order_acquire)) {
         PSD_HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
                                         hipFuncAttributeMaxDynamicSharedMemorySize, int(C::LDS_BYTES)));
-        attr_done = true;
+        attr_done.store(true, std::memory_order_release);
     }
     hipLaunchKernelGGL(kern, dim3(static_cast<uint32_t>(tiles)), dim3(C::THREADS), C::LDS_BYTES, st, U, ldu, V, ldv, W,
                        Mom, static_cast<int>(N), static_cast<int>(M), static_cast<int>(K), lr, mu,

@@ -81,6 +81,18 @@ def test_pack_bit_exact(M, N, B, P, dtype):
     assert not Ug[:, N:].any() and not Vg[:, M:].any()          # padding columns are zero
 
 
+def test_pack_maximum_worker_count():
+    d = inputs.fc_layer(40, 24, 1, 64, seed=64)                  # P = 64 workers, one sample each
+    for dtype, name in ((psd.F32, "f32"), (psd.BF16, "bf16")):
+        plan, U, ldu, V, ldv = run_pack(d, dtype)
+        Uo, Vo = orc.pack_factors(d["delta"], d["act"], name)
+        Ug = U.cpu().numpy().view(np.uint32) if dtype == psd.F32 else bits16(U)
+        Vg = V.cpu().numpy().view(np.uint32) if dtype == psd.F32 else bits16(V)
+        Uo = Uo.view(np.uint32) if dtype == psd.F32 else Uo
+        Vo = Vo.view(np.uint32) if dtype == psd.F32 else Vo
+        assert np.array_equal(Ug[:, :24], Uo) and np.array_equal(Vg[:, :40], Vo)
+
+
 def test_pack_nan_stays_nan():
     d = inputs.fc_layer(16, 8, 2, 2, seed=3)
     d["delta"][1][1, 3] = np.float32(np.nan)
@@ -163,6 +175,28 @@ def test_sfb_integer_factors_bit_exact(M, N, B, P, dtype):
     Wr, Mr = orc.sync_fc_sfb(U, V, d["W"], d["Mom"], 0.25, 0.5)
     assert np.array_equal(Mg, Mr), np.argwhere(Mg != Mr)[:8]
     assert np.array_equal(Wg, Wr)
+
+
+@pytest.mark.parametrize("tile", [0, 1, 2, 3, 4, 7])
+def test_sfb_bf16_every_tile_shape_bit_exact(tile, monkeypatch):
+    # every kernel instantiation the tile heuristic can pick (and the tuning-only ones), on a shape
+    # with ragged tiles in both directions, a K tail, and more than one tile per direction
+    monkeypatch.setenv("PSD_SFB_BF16_TILE", str(tile))
+    d = inputs.fc_layer_integer(M=520, N=300, B=11, P=5, seed=tile + 50)
+    Wg, Mg, _ = run_sfb(d, psd.BF16, 0.25, 0.5)
+    U, V = orc.pack_factors(d["delta"], d["act"])
+    Wr, Mr = orc.sync_fc_sfb(U, V, d["W"], d["Mom"], 0.25, 0.5)
+    assert np.array_equal(Mg, Mr) and np.array_equal(Wg, Wr)
+
+
+@pytest.mark.parametrize("tile", [1, 2])
+def test_sfb_f32_both_tile_shapes_bit_exact(tile, monkeypatch):
+    monkeypatch.setenv("PSD_SFB_F32_TILE", str(tile))
+    d = inputs.fc_layer_integer(M=391, N=203, B=7, P=3, seed=tile + 60)
+    Wg, Mg, _ = run_sfb(d, psd.F32, 0.25, 0.5)
+    U, V = orc.pack_factors(d["delta"], d["act"])
+    Wr, Mr = orc.sync_fc_sfb(U, V, d["W"], d["Mom"], 0.25, 0.5)
+    assert np.array_equal(Mg, Mr) and np.array_equal(Wg, Wr)
 
 
 def test_sfb_single_sample_is_exact_outer_product():
@@ -302,6 +336,31 @@ def test_iteration_scaled_down_matches_oracle_and_ignores_issue_order(factor_dty
             U, V = orc.pack_factors(L["delta"], L["act"], name)
             Wr, Mr = orc.sync_fc_sfb(U, V, L["W"], L["Mom"], inputs.LR, inputs.MU)
         e = three_errors(L["W"], Wg, Mg, Wr, Mr)
+        assert max(e) <= TOL_F32, (L["name"], e)
+
+
+def test_iteration_full_size_in_the_benchmark_configuration():
+    """Config 5 at full size, issued exactly as bench.py does (one stream per layer, Algorithm 3
+    routes, bf16 factors): conv layers compared whole, FC layers on 20 000 sampled weights each."""
+    layers = inputs.cnn_iteration()
+    streams = [torch.cuda.Stream(device=DEV) for _ in layers]
+    tasks, state = _build_iteration(layers, psd.BF16, streams)
+    torch.cuda.synchronize()
+    psd.Iteration(tasks).run(inputs.LR, inputs.MU, psd.RULE_ALG3)
+    torch.cuda.synchronize()
+    for L, (W, Mom) in zip(layers, state):
+        Wg, Mg = W.cpu().numpy(), Mom.cpu().numpy()
+        if L["kind"] == "conv":
+            Wr, Mr = orc.sync_dense_ps(L["G"], L["W"], L["Mom"], inputs.LR, inputs.MU, inputs.CNN_S)
+            e = three_errors(L["W"], Wg, Mg, Wr, Mr)
+        else:
+            idx_n, idx_m = _sample_positions(L["N"], L["M"], 20000, seed=L["N"])
+            Ub, Vb = orc.pack_factors(L["delta"], L["act"], "bf16")
+            dWs = orc.rebuild_samples(Ub, Vb, idx_n, idx_m)
+            W0s, M0s = L["W"][idx_n, idx_m], L["Mom"][idx_n, idx_m]
+            Wr, Mr = orc.momentum_update(dWs, W0s, M0s, inputs.LR, inputs.MU)
+            e = three_errors(W0s, Wg[idx_n, idx_m], Mg[idx_n, idx_m], Wr, Mr)
+            assert np.array_equal(Wg, L["W"] - Mg)      # every weight updated exactly once
         assert max(e) <= TOL_F32, (L["name"], e)
 
 
