@@ -276,6 +276,27 @@ def test_sfb_bf16_full_size_sampled(cfg):
         assert np.abs(col).max() <= 2e-2 * np.abs(Mg.astype(np.float64)).sum(axis=0).max()
 
 
+@pytest.mark.parametrize("M,N,B,P,dtype", [
+    (3000, 3000, 256, 8, psd.BF16),      # FC stack of the ImageNet-22K network (Section 5.1.3)
+    (3000, 3000, 256, 8, psd.F32),
+    (3000, 21841, 256, 8, psd.BF16),     # its 21 841-way classifier
+    (1024, 1000, 32, 8, psd.BF16),       # GoogLeNet's single FC layer at batch 32 per node (Section 5.1.2)
+    (1024, 1000, 32, 8, psd.F32),
+])
+def test_sfb_second_workload_shapes_sampled(M, N, B, P, dtype):
+    d = inputs.fc_layer(M, N, B, P, seed=M + N + B, delta_kind="softmax" if N == 21841 else "gauss")
+    Wg, Mg, _ = run_sfb(d, dtype, inputs.LR, inputs.MU)
+    idx_n, idx_m = _sample_positions(N, M, 20000, seed=N)
+    name = "f32" if dtype == psd.F32 else "bf16"
+    U, V = orc.pack_factors(d["delta"], d["act"], name)
+    dWs = orc.rebuild_samples(U, V, idx_n, idx_m)
+    W0s, M0s = d["W"][idx_n, idx_m], d["Mom"][idx_n, idx_m]
+    Wr, Mr = orc.momentum_update(dWs, W0s, M0s, inputs.LR, inputs.MU)
+    e = three_errors(W0s, Wg[idx_n, idx_m], Mg[idx_n, idx_m], Wr, Mr)
+    assert max(e) <= TOL_F32, e
+    assert np.array_equal(Wg, d["W"] - Mg)                # every weight updated exactly once
+
+
 def test_sfb_equals_ps_route_on_the_same_gradients():
     # Section 4.3.1: factors reconstruct the gradient exactly, so both routes agree
     d = inputs.fc_layer_integer(M=300, N=200, B=4, P=3, seed=31)

@@ -190,3 +190,32 @@ def test_shard_range_rejects_bad_arguments():
     for n, S, s in [(4, 5, 0), (4, 0, 0), (4, 2, 2), (4, 2, -1)]:
         with pytest.raises(ValueError):
             orc.shard_range(n, S, s)
+
+
+# ---------------------------------------------------------------------------------------
+# Fig. 4 (missing from the paper text): the three strategies between fc6 and fc7
+# (M = N = 4096) as the node count P and the per-node batch K vary.  The figure itself is
+# gone, but its caption and the paragraph after it fix what it must show.
+# ---------------------------------------------------------------------------------------
+def test_fig4_regenerated_from_the_closed_forms():
+    M = N = 4096
+    # (1) varying P at K = 256: SFB grows quadratically and eventually loses to both others
+    sfb = [orc.plan_layer(FC, M, N, 256, P)["cost_sfb"] for P in range(1, 65)]
+    dense = [orc.plan_layer(FC, M, N, 256, P)["cost_ps_dense"] for P in range(1, 65)]
+    sfps = [orc.plan_layer(FC, M, N, 256, P)["cost_sf_ps"] for P in range(1, 65)]
+    assert all(a < b for a, b in zip(sfb[:8], dense[:8]))            # small clusters: SFB wins clearly
+    first_loss_vs_sfps = next(P for P in range(1, 65) if sfb[P - 1] > sfps[P - 1])
+    first_loss_vs_dense = next(P for P in range(1, 65) if sfb[P - 1] > dense[P - 1])
+    assert first_loss_vs_sfps == 11 and first_loss_vs_dense == 18    # hand-solved from the inequalities
+    assert all(sfps[i] < dense[i] for i in range(64))                # factors-to-server always beats full matrices here
+    # (2) varying K at P = 8: "SFB usually outperforms the other two with a smaller batch size"
+    for K in (1, 16, 64, 256):
+        p = orc.plan_layer(FC, M, N, K, 8)
+        assert p["cost_sfb"] < p["cost_sf_ps"] < p["cost_ps_dense"]
+    big = orc.plan_layer(FC, M, N, 1024, 8)
+    assert big["cost_sfb"] > big["cost_sf_ps"]                        # large batches flip the choice
+    assert big["route_alg3"] == orc.ROUTE_SF_PS
+    # SFB and factors-to-server grow linearly in K, full matrices do not depend on K
+    c = [orc.plan_layer(FC, M, N, K, 8) for K in (100, 200, 300)]
+    assert c[1]["cost_sfb"] - c[0]["cost_sfb"] == c[2]["cost_sfb"] - c[1]["cost_sfb"]
+    assert c[0]["cost_ps_dense"] == c[2]["cost_ps_dense"]
