@@ -94,7 +94,10 @@ psd_status psd_pack_factors(const psd_plan* plan, const float* const* delta_p,
 
 /* SFB step 3 and Algorithm 3's update line on one worker, fused:
  *     dW[n][m] = sum_{k<K} U[k][n] * V[k][m]          (Eq. 5 summed over all P*B samples)
- *     Mom <- mu*Mom + lr*dW ;  W <- W - Mom           (momentum SGD; sum over workers, no 1/P)
+ *     Mom <- mu*Mom + lr*(dW + wd*W) ;  W <- W - Mom  (momentum SGD with L2 weight decay wd, the
+ *                                                      "regularisation and momentum" term Lambda of
+ *                                                      Section 3.3; sum over workers, no 1/P; wd = 0
+ *                                                      gives plain momentum SGD)
  * U, V [dev] as written by psd_pack_factors (same dtype and leading dimensions);
  * W, Mom [dev] N x M fp32 row-major, updated in place; dW is never stored.
  * fp32 factors: fp32 MFMA, fp32 accumulation.  bf16 factors: bf16 MFMA with fp32
@@ -102,17 +105,17 @@ psd_status psd_pack_factors(const psd_plan* plan, const float* const* delta_p,
  * runs the identical reconstruction over the same P*B factors). */
 psd_status psd_sync_fc_sfb(const psd_plan* plan, int32_t factor_dtype,
                            const void* U, int64_t ldu, const void* V, int64_t ldv,
-                           float* W, float* Mom, float lr, float mu, void* stream);
+                           float* W, float* Mom, float lr, float mu, float wd, void* stream);
 
 /* Parameter-server route (Algorithm 1 master node; Algorithm 3 non-FC branch): for every
  * key i of every shard, g = sum_{p<P} G[p][i] (summed in p order, fp32), then the same
- * momentum update on W[i], Mom[i].
+ * update (momentum mu, step lr, weight decay wd) on W[i], Mom[i].
  *   G [host] array of P [dev] pointers to n fp32 each (read only); W, Mom [dev] n fp32,
  *   in place.  1 <= P <= PSD_MAX_WORKERS; n >= 0 (n == 0 is a no-op); 1 <= S <= n.
  * The shards (psd_shard_range) are processed one after the other in key order inside one
  * launch; S changes which workgroup touches which key, never a value. */
 psd_status psd_sync_dense_ps(int64_t n, int32_t P, const float* const* G,
-                             float* W, float* Mom, float lr, float mu, int32_t S, void* stream);
+                             float* W, float* Mom, float lr, float mu, float wd, int32_t S, void* stream);
 
 /* One segment (layer) of a batched parameter-server launch. */
 typedef struct psd_dense_segment {
@@ -128,7 +131,7 @@ typedef struct psd_dense_segment {
  * layers of an AlexNet-sized net would otherwise be launch-latency bound).
  * 1 <= L <= PSD_MAX_MULTI_SEGMENTS; segs [host].  Same arithmetic as psd_sync_dense_ps. */
 psd_status psd_sync_dense_ps_multi(int32_t L, const psd_dense_segment* segs,
-                                   float lr, float mu, void* stream);
+                                   float lr, float mu, float wd, void* stream);
 
 /* One layer of an iteration for psd_sync_iteration. */
 typedef struct psd_layer_task {
@@ -155,7 +158,7 @@ typedef struct psd_layer_task {
  * psd_pack_factors then psd_sync_fc_sfb.  Layers own disjoint parameters (Section 4.2), so
  * no ordering between streams is needed; the caller synchronises the streams.
  * Stops at and returns the first error. */
-psd_status psd_sync_iteration(int32_t L, const psd_layer_task* layers, float lr, float mu,
+psd_status psd_sync_iteration(int32_t L, const psd_layer_task* layers, float lr, float mu, float wd,
                               int32_t rule);
 
 const char* psd_status_string(psd_status s);

@@ -117,15 +117,16 @@ void orc_rebuild_samples(const float* U, const float* V, int64_t K, int64_t N, i
 /* ---- momentum-SGD update ---------------------------------------------------------------
  * Section 3.3, Eq. 3-4 (additive update with step size and a momentum term) and Alg. 3's
  * update line.  Reading taken (the paper gives no explicit momentum formula):
- *   mom' = mu*mom + lr*dW ;  w' = w - mom'
+ *   mom' = mu*mom + lr*(dW + wd*w) ;  w' = w - mom'
+ * (wd = L2 weight decay, the regularisation part of Lambda; wd = 0: plain momentum SGD),
  * evaluated in float64 from the fp32 inputs, each result rounded to fp32 once.
  */
-void orc_update(const double* dW, float* W, float* Mom, float lr, float mu, int64_t count)
+void orc_update(const double* dW, float* W, float* Mom, float lr, float mu, float wd, int64_t count)
 {
-    double dlr = (double)lr, dmu = (double)mu;
+    double dlr = (double)lr, dmu = (double)mu, dwd = (double)wd;
 #pragma omp parallel for schedule(static)
     for (int64_t i = 0; i < count; ++i) {
-        double mom = dmu * (double)Mom[i] + dlr * dW[i];
+        double mom = dmu * (double)Mom[i] + dlr * (dW[i] + dwd * (double)W[i]);
         double w = (double)W[i] - mom;
         Mom[i] = (float)mom;
         W[i] = (float)w;
@@ -150,9 +151,9 @@ void orc_shard_range(int64_t n, int64_t S, int64_t s, int64_t* begin, int64_t* e
  * (Eq. 2 and Eq. 4 sum over p).
  */
 void orc_dense_ps(const float* const* G, int64_t P, int64_t n, int64_t S,
-                  float* W, float* Mom, float lr, float mu)
+                  float* W, float* Mom, float lr, float mu, float wd)
 {
-    double dlr = (double)lr, dmu = (double)mu;
+    double dlr = (double)lr, dmu = (double)mu, dwd = (double)wd;
     for (int64_t s = 0; s < S; ++s) {
         int64_t b, e;
         orc_shard_range(n, S, s, &b, &e);
@@ -160,7 +161,7 @@ void orc_dense_ps(const float* const* G, int64_t P, int64_t n, int64_t S,
         for (int64_t i = b; i < e; ++i) {
             double g = 0.0;
             for (int64_t p = 0; p < P; ++p) g += (double)G[p][i];
-            double mom = dmu * (double)Mom[i] + dlr * g;
+            double mom = dmu * (double)Mom[i] + dlr * (g + dwd * (double)W[i]);
             double w = (double)W[i] - mom;
             Mom[i] = (float)mom;
             W[i] = (float)w;

@@ -12,7 +12,9 @@ Readings of the paper used here (each is also listed in the design notes):
     per-worker batch, called B here; K = P*B is the number of stacked samples.
   * The update sums over all P workers' samples, own worker included, with no 1/P
     (Eq. 2, Eq. 4, Alg. 3 SFB branch).
-  * Lambda (momentum) is applied once per update: mom' = mu*mom + lr*dW, w' = w - mom'.
+  * Lambda ("regularisation and momentum", Section 3.3) is applied once per update:
+    mom' = mu*mom + lr*(dW + wd*w), w' = w - mom'  (L2 weight decay wd added to the gradient
+    before the momentum, as in the Caffe solver the paper builds on; wd = 0 by default).
   * Costs: SFB (P-1)^2 B (M+N); full matrices 2 P M N; factors-to-server
     P B (M+N) + P M N (Section 4.3.1).  Alg. 3 compares the first with the third and
     takes SFB on equality.
@@ -64,10 +66,10 @@ def lib():
         L.orc_bf16_widen_array.argtypes = [u16p, f32p, i64]
         L.orc_rebuild.argtypes = [f32p, f32p, i64, i64, i64, f64p]
         L.orc_rebuild_samples.argtypes = [f32p, f32p, i64, i64, i64, i64p, i64p, i64, f64p]
-        L.orc_update.argtypes = [f64p, f32p, f32p, ctypes.c_float, ctypes.c_float, i64]
+        L.orc_update.argtypes = [f64p, f32p, f32p, ctypes.c_float, ctypes.c_float, ctypes.c_float, i64]
         L.orc_shard_range.argtypes = [i64, i64, i64, i64p, i64p]
         L.orc_dense_ps.argtypes = [ctypes.POINTER(f32p), i64, i64, i64, f32p, f32p,
-                                   ctypes.c_float, ctypes.c_float]
+                                   ctypes.c_float, ctypes.c_float, ctypes.c_float]
         for fn in (L.orc_bf16_round_array, L.orc_bf16_widen_array, L.orc_rebuild,
                    L.orc_rebuild_samples, L.orc_update, L.orc_shard_range, L.orc_dense_ps):
             fn.restype = None
@@ -216,8 +218,8 @@ def rebuild_samples(U, V, idx_n, idx_m):
     return out
 
 
-def momentum_update(dW, W, Mom, lr, mu):
-    """Returns (W', Mom') as new float32 arrays; mom' = mu*mom + lr*dW, w' = w - mom'."""
+def momentum_update(dW, W, Mom, lr, mu, wd=0.0):
+    """Returns (W', Mom') as new float32 arrays; mom' = mu*mom + lr*(dW + wd*w), w' = w - mom'."""
     dW = np.ascontiguousarray(dW, dtype=np.float64)
     W2 = np.array(W, dtype=np.float32, copy=True, order="C")
     Mom2 = np.array(Mom, dtype=np.float32, copy=True, order="C")
@@ -225,21 +227,16 @@ def momentum_update(dW, W, Mom, lr, mu):
     lib().orc_update(dW.ctypes.data_as(ctypes.POINTER(ctypes.c_double)),
                      W2.ctypes.data_as(ctypes.POINTER(ctypes.c_float)),
                      Mom2.ctypes.data_as(ctypes.POINTER(ctypes.c_float)),
-                     np.float32(lr), np.float32(mu), W2.size)
+                     np.float32(lr), np.float32(mu), np.float32(wd), W2.size)
     return W2, Mom2
 
 
-def momentum_update_samples(dW_s, W_s, Mom_s, lr, mu):
-    """Same formula on gathered samples (float64 in, float32 out)."""
-    return momentum_update(np.asarray(dW_s), np.asarray(W_s), np.asarray(Mom_s), lr, mu)
-
-
-def sync_fc_sfb(U, V, W, Mom, lr, mu):
+def sync_fc_sfb(U, V, W, Mom, lr, mu, wd=0.0):
     """Alg. 3 SFB branch on one worker: rebuild from all stacked factors, then update."""
-    return momentum_update(rebuild(U, V), W, Mom, lr, mu)
+    return momentum_update(rebuild(U, V), W, Mom, lr, mu, wd)
 
 
-def sync_dense_ps(G, W, Mom, lr, mu, S=1):
+def sync_dense_ps(G, W, Mom, lr, mu, S=1, wd=0.0):
     """Server side of the PS route: per key-range shard, sum the P copies and update."""
     P = len(G)
     Gc = [np.ascontiguousarray(g, dtype=np.float32).ravel() for g in G]
@@ -252,7 +249,7 @@ def sync_dense_ps(G, W, Mom, lr, mu, S=1):
     f32p = ctypes.POINTER(ctypes.c_float)
     ptrs = (f32p * P)(*[g.ctypes.data_as(f32p) for g in Gc])
     lib().orc_dense_ps(ptrs, P, n, S, W2.ctypes.data_as(f32p), Mom2.ctypes.data_as(f32p),
-                       np.float32(lr), np.float32(mu))
+                       np.float32(lr), np.float32(mu), np.float32(wd))
     return W2, Mom2
 
 

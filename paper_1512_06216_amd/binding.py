@@ -73,13 +73,14 @@ SIGNATURES = {
                                           ctypes.c_int64, ctypes.c_void_p, ctypes.c_int64, ctypes.c_void_p]),
     "psd_sync_fc_sfb": (ctypes.c_int32, [ctypes.POINTER(Plan), ctypes.c_int32, ctypes.c_void_p, ctypes.c_int64,
                                          ctypes.c_void_p, ctypes.c_int64, ctypes.c_void_p, ctypes.c_void_p,
-                                         ctypes.c_float, ctypes.c_float, ctypes.c_void_p]),
+                                         ctypes.c_float, ctypes.c_float, ctypes.c_float, ctypes.c_void_p]),
     "psd_sync_dense_ps": (ctypes.c_int32, [ctypes.c_int64, ctypes.c_int32, _f32pp, ctypes.c_void_p, ctypes.c_void_p,
-                                           ctypes.c_float, ctypes.c_float, ctypes.c_int32, ctypes.c_void_p]),
+                                           ctypes.c_float, ctypes.c_float, ctypes.c_float, ctypes.c_int32,
+                                           ctypes.c_void_p]),
     "psd_sync_dense_ps_multi": (ctypes.c_int32, [ctypes.c_int32, ctypes.POINTER(DenseSegment), ctypes.c_float,
-                                                 ctypes.c_float, ctypes.c_void_p]),
+                                                 ctypes.c_float, ctypes.c_float, ctypes.c_void_p]),
     "psd_sync_iteration": (ctypes.c_int32, [ctypes.c_int32, ctypes.POINTER(LayerTask), ctypes.c_float,
-                                            ctypes.c_float, ctypes.c_int32]),
+                                            ctypes.c_float, ctypes.c_float, ctypes.c_int32]),
     "psd_status_string": (ctypes.c_char_p, [ctypes.c_int32]),
     "psd_last_hip_error": (ctypes.c_int32, []),
     "psd_version": (ctypes.c_int32, []),
@@ -177,24 +178,25 @@ def pack_factors(plan, delta, act, out_dtype, U, ldu, V, ldv, stream=None):
            "psd_pack_factors")
 
 
-def sync_fc_sfb(plan, factor_dtype, U, ldu, V, ldv, W, Mom, lr, mu, stream=None):
+def sync_fc_sfb(plan, factor_dtype, U, ldu, V, ldv, W, Mom, lr, mu, stream=None, wd=0.0):
     up = _dev_ptr(U, _FACTOR_TORCH.get(factor_dtype, ()), plan.K * ldu, "U")
     vp = _dev_ptr(V, _FACTOR_TORCH.get(factor_dtype, ()), plan.K * ldv, "V")
     wp = _dev_ptr(W, torch.float32, plan.N * plan.M, "W")
     mp = _dev_ptr(Mom, torch.float32, plan.N * plan.M, "Mom")
-    _check(lib().psd_sync_fc_sfb(ctypes.byref(plan), factor_dtype, up, ldu, vp, ldv, wp, mp, lr, mu,
+    _check(lib().psd_sync_fc_sfb(ctypes.byref(plan), factor_dtype, up, ldu, vp, ldv, wp, mp, lr, mu, wd,
                                  _stream_handle(stream)), "psd_sync_fc_sfb")
 
 
-def sync_dense_ps(G, W, Mom, lr, mu, S, stream=None):
+def sync_dense_ps(G, W, Mom, lr, mu, S, stream=None, wd=0.0):
     n = W.numel()
     g = _ptr_array(G, n, "G")
     wp = _dev_ptr(W, torch.float32, n, "W")
     mp = _dev_ptr(Mom, torch.float32, n, "Mom")
-    _check(lib().psd_sync_dense_ps(n, len(G), g, wp, mp, lr, mu, S, _stream_handle(stream)), "psd_sync_dense_ps")
+    _check(lib().psd_sync_dense_ps(n, len(G), g, wp, mp, lr, mu, wd, S, _stream_handle(stream)),
+           "psd_sync_dense_ps")
 
 
-def sync_dense_ps_multi(layers, lr, mu, stream=None):
+def sync_dense_ps_multi(layers, lr, mu, stream=None, wd=0.0):
     """layers: list of (G_list, W, Mom, S)."""
     segs = (DenseSegment * len(layers))()
     keep = []
@@ -206,7 +208,7 @@ def sync_dense_ps_multi(layers, lr, mu, stream=None):
         segs[i].G = ctypes.cast(g, _f32pp)
         segs[i].W = ctypes.cast(_dev_ptr(W, torch.float32, n, "W"), _f32p)
         segs[i].Mom = ctypes.cast(_dev_ptr(Mom, torch.float32, n, "Mom"), _f32p)
-    _check(lib().psd_sync_dense_ps_multi(len(layers), segs, lr, mu, _stream_handle(stream)),
+    _check(lib().psd_sync_dense_ps_multi(len(layers), segs, lr, mu, wd, _stream_handle(stream)),
            "psd_sync_dense_ps_multi")
 
 
@@ -247,5 +249,5 @@ class Iteration:
                 t.V, t.ldv = _dev_ptr(L["V"], fd, plan.K * L["ldv"], "V"), L["ldv"]
         self.L = len(layers)
 
-    def run(self, lr, mu, rule=RULE_ALG3):
-        _check(lib().psd_sync_iteration(self.L, self.tasks, lr, mu, rule), "psd_sync_iteration")
+    def run(self, lr, mu, rule=RULE_ALG3, wd=0.0):
+        _check(lib().psd_sync_iteration(self.L, self.tasks, lr, mu, wd, rule), "psd_sync_iteration")

@@ -36,16 +36,16 @@ __device__ __forceinline__ float4 ld_stream(const float* p)
     return make_float4(v.x, v.y, v.z, v.w);
 }
 
-__device__ __forceinline__ void update1(float g, float& w, float& mom, float lr, float mu)
+__device__ __forceinline__ void update1(float g, float& w, float& mom, float lr, float mu, float wd)
 {
-    mom = __fmaf_rn(mu, mom, lr * g);
+    mom = __fmaf_rn(mu, mom, lr * __fmaf_rn(wd, w, g));   // wd = 0 leaves g unchanged
     w = w - mom;
 }
 
 // keys [lo, hi) of one layer; PC > 0: number of copies known at compile time
 template <int PC>
 __device__ __forceinline__ void dense_span(const float* const* __restrict__ G, int P, float* __restrict__ W,
-                                           float* __restrict__ Mom, int64_t lo, int64_t hi, float lr, float mu)
+                                           float* __restrict__ Mom, int64_t lo, int64_t hi, float lr, float mu, float wd)
 {
     const int nP = PC > 0 ? PC : P;
     // W, Mom and every G[p] are 16-byte aligned, so key i is float4-aligned iff i % 4 == 0
@@ -84,10 +84,10 @@ __device__ __forceinline__ void dense_span(const float* const* __restrict__ G, i
 #pragma unroll
     for (int u = 0; u < kDenseUnroll; ++u) {
         if (idx[u] < hi4) {
-            update1(acc[u].x, w[u].x, m[u].x, lr, mu);
-            update1(acc[u].y, w[u].y, m[u].y, lr, mu);
-            update1(acc[u].z, w[u].z, m[u].z, lr, mu);
-            update1(acc[u].w, w[u].w, m[u].w, lr, mu);
+            update1(acc[u].x, w[u].x, m[u].x, lr, mu, wd);
+            update1(acc[u].y, w[u].y, m[u].y, lr, mu, wd);
+            update1(acc[u].z, w[u].z, m[u].z, lr, mu, wd);
+            update1(acc[u].w, w[u].w, m[u].w, lr, mu, wd);
             *reinterpret_cast<float4*>(Mom + idx[u]) = m[u];
             *reinterpret_cast<float4*>(W + idx[u]) = w[u];
         }
@@ -100,14 +100,14 @@ __device__ __forceinline__ void dense_span(const float* const* __restrict__ G, i
         float g = G[0][i];
         for (int p = 1; p < nP; ++p) g += G[p][i];
         float wv = W[i], mv = Mom[i];
-        update1(g, wv, mv, lr, mu);
+        update1(g, wv, mv, lr, mu, wd);
         Mom[i] = mv;
         W[i] = wv;
     }
 }
 
 __device__ __forceinline__ void dense_block(const float* const* G, int P, float* W, float* Mom, int64_t q, int64_t r, int S,
-                                            int chunks, int local_block, float lr, float mu)
+                                            int chunks, int local_block, float lr, float mu, float wd)
 {
     const int s = local_block / chunks;
     const int64_t c = local_block % chunks;
@@ -128,15 +128,15 @@ __device__ __forceinline__ void dense_block(const float* const* G, int P, float*
     if (lo >= end) return;
     const int64_t hi = lo + kDenseChunk < end ? lo + kDenseChunk : end;
     switch (P) {
-        case 8: dense_span<8>(G, P, W, Mom, lo, hi, lr, mu); break;
-        case 4: dense_span<4>(G, P, W, Mom, lo, hi, lr, mu); break;
-        case 2: dense_span<2>(G, P, W, Mom, lo, hi, lr, mu); break;
-        case 16: dense_span<16>(G, P, W, Mom, lo, hi, lr, mu); break;
-        default: dense_span<0>(G, P, W, Mom, lo, hi, lr, mu); break;
+        case 8: dense_span<8>(G, P, W, Mom, lo, hi, lr, mu, wd); break;
+        case 4: dense_span<4>(G, P, W, Mom, lo, hi, lr, mu, wd); break;
+        case 2: dense_span<2>(G, P, W, Mom, lo, hi, lr, mu, wd); break;
+        case 16: dense_span<16>(G, P, W, Mom, lo, hi, lr, mu, wd); break;
+        default: dense_span<0>(G, P, W, Mom, lo, hi, lr, mu, wd); break;
     }
 }
 
-__global__ void __launch_bounds__(kDenseThreads) dense_ps_table_kernel(const DenseTable t, float lr, float mu)
+__global__ void __launch_bounds__(kDenseThreads) dense_ps_table_kernel(const DenseTable t, float lr, float mu, float wd)
 {
     // which layer does this workgroup belong to (at most 16 segments: linear scan)
     int l = 0;
@@ -144,28 +144,28 @@ __global__ void __launch_bounds__(kDenseThreads) dense_ps_table_kernel(const Den
     for (int j = 1; j < t.L; ++j)
         if (b >= t.seg[j].block_begin) l = j;
     const DenseSeg& sg = t.seg[l];
-    dense_block(sg.G, sg.P, sg.W, sg.Mom, sg.q, sg.r, sg.S, sg.chunks, b - sg.block_begin, lr, mu);
+    dense_block(sg.G, sg.P, sg.W, sg.Mom, sg.q, sg.r, sg.S, sg.chunks, b - sg.block_begin, lr, mu, wd);
 }
 
-__global__ void __launch_bounds__(kDenseThreads) dense_ps_wide_kernel(const DenseWide a, float lr, float mu)
+__global__ void __launch_bounds__(kDenseThreads) dense_ps_wide_kernel(const DenseWide a, float lr, float mu, float wd)
 {
-    dense_block(a.G, a.P, a.W, a.Mom, a.q, a.r, a.S, a.chunks, blockIdx.x, lr, mu);
+    dense_block(a.G, a.P, a.W, a.Mom, a.q, a.r, a.S, a.chunks, blockIdx.x, lr, mu, wd);
 }
 
 }  // namespace
 
-psd_status launch_dense_table(const DenseTable& t, int32_t total_blocks, float lr, float mu, hipStream_t st)
+psd_status launch_dense_table(const DenseTable& t, int32_t total_blocks, float lr, float mu, float wd, hipStream_t st)
 {
-    hipLaunchKernelGGL(dense_ps_table_kernel, dim3(total_blocks), dim3(kDenseThreads), 0, st, t, lr, mu);
+    hipLaunchKernelGGL(dense_ps_table_kernel, dim3(total_blocks), dim3(kDenseThreads), 0, st, t, lr, mu, wd);
     PSD_HIP_TRY(hipGetLastError());
     return PSD_OK;
 }
 
-psd_status launch_dense_wide(const DenseWide& a, float lr, float mu, hipStream_t st)
+psd_status launch_dense_wide(const DenseWide& a, float lr, float mu, float wd, hipStream_t st)
 {
     const int64_t blocks = int64_t(a.chunks) * a.S;
     if (blocks < 1 || blocks > (int64_t(1) << 30)) return PSD_E_INVALID;
-    hipLaunchKernelGGL(dense_ps_wide_kernel, dim3(static_cast<uint32_t>(blocks)), dim3(kDenseThreads), 0, st, a, lr, mu);
+    hipLaunchKernelGGL(dense_ps_wide_kernel, dim3(static_cast<uint32_t>(blocks)), dim3(kDenseThreads), 0, st, a, lr, mu, wd);
     PSD_HIP_TRY(hipGetLastError());
     return PSD_OK;
 }

@@ -127,10 +127,11 @@ psd_status psd_pack_factors(const psd_plan* plan, const float* const* delta_p, c
 }
 
 psd_status psd_sync_fc_sfb(const psd_plan* plan, int32_t factor_dtype, const void* U, int64_t ldu,
-                           const void* V, int64_t ldv, float* W, float* Mom, float lr, float mu, void* stream)
+                           const void* V, int64_t ldv, float* W, float* Mom, float lr, float mu, float wd, void* stream)
 {
     if (!plan || !U || !V || !W || !Mom) return PSD_E_NULL;
     if (factor_dtype != PSD_F32 && factor_dtype != PSD_BF16) return PSD_E_INVALID;
+    if (!(wd >= 0.0f)) return PSD_E_INVALID;          // also rejects NaN
     if (!valid_plan_sizes(plan)) return PSD_E_INVALID;
     if (!valid_ld(ldu, plan->N, factor_dtype) || !valid_ld(ldv, plan->M, factor_dtype)) return PSD_E_INVALID;
     if (!aligned16(U) || !aligned16(V) || !aligned16(W) || !aligned16(Mom)) return PSD_E_INVALID;
@@ -139,9 +140,9 @@ psd_status psd_sync_fc_sfb(const psd_plan* plan, int32_t factor_dtype, const voi
     const int64_t K = plan->P * plan->B;
     if (factor_dtype == PSD_F32)
         return launch_sfb_f32(static_cast<const float*>(U), ldu, static_cast<const float*>(V), ldv, W, Mom,
-                              plan->N, plan->M, K, lr, mu, st);
+                              plan->N, plan->M, K, lr, mu, wd, st);
     return launch_sfb_bf16(static_cast<const uint16_t*>(U), ldu, static_cast<const uint16_t*>(V), ldv, W, Mom,
-                           plan->N, plan->M, K, lr, mu, st);
+                           plan->N, plan->M, K, lr, mu, wd, st);
 }
 
 static psd_status check_dense(int64_t n, int32_t P, int32_t maxP, const float* const* G, const float* W,
@@ -160,8 +161,9 @@ static psd_status check_dense(int64_t n, int32_t P, int32_t maxP, const float* c
 }
 
 psd_status psd_sync_dense_ps(int64_t n, int32_t P, const float* const* G, float* W, float* Mom,
-                             float lr, float mu, int32_t S, void* stream)
+                             float lr, float mu, float wd, int32_t S, void* stream)
 {
+    if (!(wd >= 0.0f)) return PSD_E_INVALID;
     psd_status r = check_dense(n, P, PSD_MAX_WORKERS, G, W, Mom, S);
     if (r != PSD_OK) return r;
     if (n == 0) return PSD_OK;
@@ -170,13 +172,13 @@ psd_status psd_sync_dense_ps(int64_t n, int32_t P, const float* const* G, float*
     a.W = W; a.Mom = Mom; a.n = n; a.P = P; a.S = S;
     a.q = n / S; a.r = n % S;
     a.chunks = dense_chunks_for(n, S);
-    return launch_dense_wide(a, lr, mu, static_cast<hipStream_t>(stream));
+    return launch_dense_wide(a, lr, mu, wd, static_cast<hipStream_t>(stream));
 }
 
-psd_status psd_sync_dense_ps_multi(int32_t L, const psd_dense_segment* segs, float lr, float mu, void* stream)
+psd_status psd_sync_dense_ps_multi(int32_t L, const psd_dense_segment* segs, float lr, float mu, float wd, void* stream)
 {
     if (!segs) return PSD_E_NULL;
-    if (L < 1 || L > PSD_MAX_MULTI_SEGMENTS) return PSD_E_INVALID;
+    if (L < 1 || L > PSD_MAX_MULTI_SEGMENTS || !(wd >= 0.0f)) return PSD_E_INVALID;
     DenseTable t;
     int64_t blocks = 0;
     int32_t used = 0;
@@ -196,12 +198,12 @@ psd_status psd_sync_dense_ps_multi(int32_t L, const psd_dense_segment* segs, flo
     }
     if (used == 0) return PSD_OK;
     t.L = used;
-    return launch_dense_table(t, static_cast<int32_t>(blocks), lr, mu, static_cast<hipStream_t>(stream));
+    return launch_dense_table(t, static_cast<int32_t>(blocks), lr, mu, wd, static_cast<hipStream_t>(stream));
 }
 
 // Algorithm 2's order: the top layer's gradient exists first, so its synchronisation is
 // issued first; every layer goes to its own stream.
-psd_status psd_sync_iteration(int32_t L, const psd_layer_task* layers, float lr, float mu, int32_t rule)
+psd_status psd_sync_iteration(int32_t L, const psd_layer_task* layers, float lr, float mu, float wd, int32_t rule)
 {
     if (!layers) return PSD_E_NULL;
     if (L < 1 || (rule != PSD_RULE_ALG3 && rule != PSD_RULE_SFB_VS_DENSE)) return PSD_E_INVALID;
@@ -218,13 +220,13 @@ psd_status psd_sync_iteration(int32_t L, const psd_layer_task* layers, float lr,
                 return PSD_E_INVALID;
             if (t.ev_begin) PSD_HIP_TRY(hipEventRecord(static_cast<hipEvent_t>(t.ev_begin), st));
             r = psd_sync_dense_ps(static_cast<int64_t>(n), static_cast<int32_t>(t.plan.P), t.G, t.W, t.Mom,
-                                  lr, mu, t.S, t.stream);
+                                  lr, mu, wd, t.S, t.stream);
         } else if (route == PSD_ROUTE_SFB || route == PSD_ROUTE_SF_PS) {
             if (t.plan.kind != PSD_LAYER_FC) return PSD_E_INVALID;
             r = psd_pack_factors(&t.plan, t.delta_p, t.act_p, t.factor_dtype, t.U, t.ldu, t.V, t.ldv, t.stream);
             if (r == PSD_OK && t.ev_begin) PSD_HIP_TRY(hipEventRecord(static_cast<hipEvent_t>(t.ev_begin), st));
             if (r == PSD_OK)
-                r = psd_sync_fc_sfb(&t.plan, t.factor_dtype, t.U, t.ldu, t.V, t.ldv, t.W, t.Mom, lr, mu, t.stream);
+                r = psd_sync_fc_sfb(&t.plan, t.factor_dtype, t.U, t.ldu, t.V, t.ldv, t.W, t.Mom, lr, mu, wd, t.stream);
         } else {
             return PSD_E_INVALID;
         }

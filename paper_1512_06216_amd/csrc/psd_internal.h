@@ -43,8 +43,8 @@ struct DenseWide {          // single layer, up to PSD_MAX_WORKERS copies
     int32_t S;
     int32_t chunks;
 };
-psd_status launch_dense_table(const DenseTable& t, int32_t total_blocks, float lr, float mu, hipStream_t st);
-psd_status launch_dense_wide(const DenseWide& a, float lr, float mu, hipStream_t st);
+psd_status launch_dense_table(const DenseTable& t, int32_t total_blocks, float lr, float mu, float wd, hipStream_t st);
+psd_status launch_dense_wide(const DenseWide& a, float lr, float mu, float wd, hipStream_t st);
 int32_t dense_chunks_for(int64_t n, int32_t S);   // workgroups per shard
 
 struct PackArgs {
@@ -56,8 +56,8 @@ struct PackArgs {
 psd_status launch_pack(const PackArgs& a, int32_t out_dtype, hipStream_t st);
 
 psd_status launch_sfb_f32(const float* U, int64_t ldu, const float* V, int64_t ldv, float* W, float* Mom,
-                          int64_t N, int64_t M, int64_t K, float lr, float mu, hipStream_t st);
+                          int64_t N, int64_t M, int64_t K, float lr, float mu, float wd, hipStream_t st);
 psd_status launch_sfb_bf16(const uint16_t* U, int64_t ldu, const uint16_t* V, int64_t ldv, float* W, float* Mom,
-                           int64_t N, int64_t M, int64_t K, float lr, float mu, hipStream_t st);
+                           int64_t N, int64_t M, int64_t K, float lr, float mu, float wd, hipStream_t st);
 
 }  // namespace psd

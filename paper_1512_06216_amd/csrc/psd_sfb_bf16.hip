@@ -87,9 +87,9 @@ __device__ __forceinline__ bf16x4 read_tr(uint32_t lds_addr)
     return __builtin_amdgcn_ds_read_tr16_b64_v4bf16(reinterpret_cast<lds_bf16x4*>(lds_addr));
 }
 
-__device__ __forceinline__ void upd(float d, float& w, float& mo, float lr, float mu)
+__device__ __forceinline__ void upd(float d, float& w, float& mo, float lr, float mu, float wd)
 {
-    mo = __fmaf_rn(mu, mo, lr * d);
+    mo = __fmaf_rn(mu, mo, lr * __fmaf_rn(wd, w, d));   // wd = 0 leaves d unchanged
     w = w - mo;
 }
 
@@ -109,7 +109,7 @@ __device__ __forceinline__ void interleave_groups()
 template <class C>
 __global__ void __launch_bounds__(C::THREADS, C::OCC)
 sfb_bf16_kernel(const uint16_t* __restrict__ U, int64_t ldu, const uint16_t* __restrict__ V, int64_t ldv,
-                float* __restrict__ W, float* __restrict__ Mom, int N, int M, int K, float lr, float mu,
+                float* __restrict__ W, float* __restrict__ Mom, int N, int M, int K, float lr, float mu, float wd,
                 int tiles_n, int tiles_m, uint32_t u_bytes, uint32_t v_bytes)
 {
     extern __shared__ __attribute__((aligned(1024))) uint16_t lds[];
@@ -296,10 +296,10 @@ sfb_bf16_kernel(const uint16_t* __restrict__ U, int64_t ldu, const uint16_t* __r
                 for (int jj = 0; jj < 4; ++jj) {
                     const int64_t n = n0 + wn0 + 32 * bn + prow + 8 * jj;
                     if (n < N && m < M) {
-                        upd(d[jj].x, w[jj].x, mo[jj].x, lr, mu);
-                        upd(d[jj].y, w[jj].y, mo[jj].y, lr, mu);
-                        upd(d[jj].z, w[jj].z, mo[jj].z, lr, mu);
-                        upd(d[jj].w, w[jj].w, mo[jj].w, lr, mu);
+                        upd(d[jj].x, w[jj].x, mo[jj].x, lr, mu, wd);
+                        upd(d[jj].y, w[jj].y, mo[jj].y, lr, mu, wd);
+                        upd(d[jj].z, w[jj].z, mo[jj].z, lr, mu, wd);
+                        upd(d[jj].w, w[jj].w, mo[jj].w, lr, mu, wd);
                         *reinterpret_cast<float4*>(Mom + n * int64_t(M) + m) = mo[jj];
                         *reinterpret_cast<float4*>(W + n * int64_t(M) + m) = w[jj];
                     }
@@ -321,7 +321,7 @@ sfb_bf16_kernel(const uint16_t* __restrict__ U, int64_t ldu, const uint16_t* __r
                     const int64_t m = m0 + wm0 + 32 * bm + 8 * (r >> 2) + 4 * lhi + (r & 3);
                     if (m < M) {
                         float wv = wrow[m], mv = mrow[m];
-                        upd(acc[bn][bm][r], wv, mv, lr, mu);
+                        upd(acc[bn][bm][r], wv, mv, lr, mu, wd);
                         mrow[m] = mv;
                         wrow[m] = wv;
                     }
@@ -332,7 +332,7 @@ sfb_bf16_kernel(const uint16_t* __restrict__ U, int64_t ldu, const uint16_t* __r
 
 template <class C>
 psd_status launch_cfg(const uint16_t* U, int64_t ldu, const uint16_t* V, int64_t ldv, float* W, float* Mom,
-                      int64_t N, int64_t M, int64_t K, float lr, float mu, hipStream_t st)
+                      int64_t N, int64_t M, int64_t K, float lr, float mu, float wd, hipStream_t st)
 {
     const int64_t tiles_n = (N + C::TN - 1) / C::TN, tiles_m = (M + C::TM - 1) / C::TM;
     const int64_t tiles = tiles_n * tiles_m;
@@ -351,7 +351,7 @@ psd_status launch_cfg(const uint16_t* U, int64_t ldu, const uint16_t* V, int64_t
         attr_done.store(true, std::memory_order_release);
     }
     hipLaunchKernelGGL(kern, dim3(static_cast<uint32_t>(tiles)), dim3(C::THREADS), C::LDS_BYTES, st, U, ldu, V, ldv, W,
-                       Mom, static_cast<int>(N), static_cast<int>(M), static_cast<int>(K), lr, mu,
+                       Mom, static_cast<int>(N), static_cast<int>(M), static_cast<int>(K), lr, mu, wd,
                        static_cast<int>(tiles_n), static_cast<int>(tiles_m), static_cast<uint32_t>(u_bytes),
                        static_cast<uint32_t>(v_bytes));
     PSD_HIP_TRY(hipGetLastError());
@@ -370,7 +370,7 @@ using Cfg128x192w4 = Cfg<2, 2, 2, 3, 4, 2>;   // 4 wavefronts of 64 x 96, 4 stag
 }  // namespace
 
 psd_status launch_sfb_bf16(const uint16_t* U, int64_t ldu, const uint16_t* V, int64_t ldv, float* W, float* Mom,
-                           int64_t N, int64_t M, int64_t K, float lr, float mu, hipStream_t st)
+                           int64_t N, int64_t M, int64_t K, float lr, float mu, float wd, hipStream_t st)
 {
     // PSD_SFB_BF16_TILE overrides the tile choice (tuning aid): index into the switch below
     const char* e = std::getenv("PSD_SFB_BF16_TILE");
@@ -392,14 +392,14 @@ psd_status launch_sfb_bf16(const uint16_t* U, int64_t ldu, const uint16_t* V, in
         }
     }
     switch (pick) {
-        case 0: return launch_cfg<Cfg256x256w4>(U, ldu, V, ldv, W, Mom, N, M, K, lr, mu, st);
-        case 1: return launch_cfg<Cfg256x128w4>(U, ldu, V, ldv, W, Mom, N, M, K, lr, mu, st);
-        case 2: return launch_cfg<Cfg128x256w4>(U, ldu, V, ldv, W, Mom, N, M, K, lr, mu, st);
-        case 3: return launch_cfg<Cfg256x256w8>(U, ldu, V, ldv, W, Mom, N, M, K, lr, mu, st);
-        case 4: return launch_cfg<Cfg128x128w4>(U, ldu, V, ldv, W, Mom, N, M, K, lr, mu, st);
-        case 5: return launch_cfg<Cfg128x128w4s3>(U, ldu, V, ldv, W, Mom, N, M, K, lr, mu, st);
-        case 6: return launch_cfg<Cfg128x64w4s3>(U, ldu, V, ldv, W, Mom, N, M, K, lr, mu, st);
-        case 7: return launch_cfg<Cfg128x192w4>(U, ldu, V, ldv, W, Mom, N, M, K, lr, mu, st);
+        case 0: return launch_cfg<Cfg256x256w4>(U, ldu, V, ldv, W, Mom, N, M, K, lr, mu, wd, st);
+        case 1: return launch_cfg<Cfg256x128w4>(U, ldu, V, ldv, W, Mom, N, M, K, lr, mu, wd, st);
+        case 2: return launch_cfg<Cfg128x256w4>(U, ldu, V, ldv, W, Mom, N, M, K, lr, mu, wd, st);
+        case 3: return launch_cfg<Cfg256x256w8>(U, ldu, V, ldv, W, Mom, N, M, K, lr, mu, wd, st);
+        case 4: return launch_cfg<Cfg128x128w4>(U, ldu, V, ldv, W, Mom, N, M, K, lr, mu, wd, st);
+        case 5: return launch_cfg<Cfg128x128w4s3>(U, ldu, V, ldv, W, Mom, N, M, K, lr, mu, wd, st);
+        case 6: return launch_cfg<Cfg128x64w4s3>(U, ldu, V, ldv, W, Mom, N, M, K, lr, mu, wd, st);
+        case 7: return launch_cfg<Cfg128x192w4>(U, ldu, V, ldv, W, Mom, N, M, K, lr, mu, wd, st);
         default: return PSD_E_INVALID;
     }
 }

@@ -33,9 +33,9 @@ constexpr int KT = 16;              // k rows per LDS stage
 constexpr int THREADS = 256;
 constexpr int NSTAGE = 4;           // ring depth
 
-__device__ __forceinline__ void upd(float d, float& w, float& mo, float lr, float mu)
+__device__ __forceinline__ void upd(float d, float& w, float& mo, float lr, float mu, float wd)
 {
-    mo = __fmaf_rn(mu, mo, lr * d);
+    mo = __fmaf_rn(mu, mo, lr * __fmaf_rn(wd, w, d));   // wd = 0 leaves d unchanged
     w = w - mo;
 }
 
@@ -83,7 +83,7 @@ __device__ __forceinline__ void interleave_groups()
 template <int BN>
 __global__ void __launch_bounds__(THREADS)
 sfb_f32_kernel(const float* __restrict__ U, int64_t ldu, const float* __restrict__ V, int64_t ldv,
-               float* __restrict__ W, float* __restrict__ Mom, int N, int M, int K, float lr, float mu,
+               float* __restrict__ W, float* __restrict__ Mom, int N, int M, int K, float lr, float mu, float wd,
                int tiles_m, uint32_t u_bytes, uint32_t v_bytes)
 {
     constexpr int TN = 64 * BN;
@@ -202,20 +202,20 @@ sfb_f32_kernel(const float* __restrict__ U, int64_t ldu, const float* __restrict
             float* mp = Mom + n * int64_t(M) + mcol;
             if (pair_ok && mcol + 1 < M) {
                 float2 w = *reinterpret_cast<float2*>(wp), mo = *reinterpret_cast<float2*>(mp);
-                upd(d0, w.x, mo.x, lr, mu);
-                upd(d1, w.y, mo.y, lr, mu);
+                upd(d0, w.x, mo.x, lr, mu, wd);
+                upd(d1, w.y, mo.y, lr, mu, wd);
                 *reinterpret_cast<float2*>(mp) = mo;
                 *reinterpret_cast<float2*>(wp) = w;
             } else {
                 if (mcol < M) {
                     float w = wp[0], mo = mp[0];
-                    upd(d0, w, mo, lr, mu);
+                    upd(d0, w, mo, lr, mu, wd);
                     mp[0] = mo;
                     wp[0] = w;
                 }
                 if (mcol + 1 < M) {
                     float w = wp[1], mo = mp[1];
-                    upd(d1, w, mo, lr, mu);
+                    upd(d1, w, mo, lr, mu, wd);
                     mp[1] = mo;
                     wp[1] = w;
                 }
@@ -226,7 +226,7 @@ sfb_f32_kernel(const float* __restrict__ U, int64_t ldu, const float* __restrict
 
 template <int BN>
 psd_status launch_f32(const float* U, int64_t ldu, const float* V, int64_t ldv, float* W, float* Mom,
-                      int64_t N, int64_t M, int64_t K, float lr, float mu, hipStream_t st)
+                      int64_t N, int64_t M, int64_t K, float lr, float mu, float wd, hipStream_t st)
 {
     constexpr int TN = 64 * BN;
     const int64_t tiles_n = (N + TN - 1) / TN, tiles_m = (M + TM - 1) / TM;
@@ -237,7 +237,7 @@ psd_status launch_f32(const float* U, int64_t ldu, const float* V, int64_t ldv, 
     const int64_t reach = (int64_t(1) << 32) - (NSTAGE + 2) * KT * (ldu > ldv ? ldu : ldv) * 4 - 4096;
     if (u_bytes > reach || v_bytes > reach) return PSD_E_UNSUPPORTED;
     hipLaunchKernelGGL(sfb_f32_kernel<BN>, dim3(static_cast<uint32_t>(tiles)), dim3(THREADS), 0, st, U, ldu, V, ldv, W,
-                       Mom, static_cast<int>(N), static_cast<int>(M), static_cast<int>(K), lr, mu,
+                       Mom, static_cast<int>(N), static_cast<int>(M), static_cast<int>(K), lr, mu, wd,
                        static_cast<int>(tiles_m), static_cast<uint32_t>(u_bytes), static_cast<uint32_t>(v_bytes));
     PSD_HIP_TRY(hipGetLastError());
     return PSD_OK;
@@ -246,7 +246,7 @@ psd_status launch_f32(const float* U, int64_t ldu, const float* V, int64_t ldv, 
 }  // namespace
 
 psd_status launch_sfb_f32(const float* U, int64_t ldu, const float* V, int64_t ldv, float* W, float* Mom,
-                          int64_t N, int64_t M, int64_t K, float lr, float mu, hipStream_t st)
+                          int64_t N, int64_t M, int64_t K, float lr, float mu, float wd, hipStream_t st)
 {
     // 128 x 128 tiles unless that leaves fewer than two workgroups per compute unit (one workgroup's
     // four wavefronts cannot hide LDS and barrier latency on their own)
@@ -255,8 +255,8 @@ psd_status launch_sfb_f32(const float* U, int64_t ldu, const float* V, int64_t l
     const int64_t tiles128 = ((N + 127) / 128) * ((M + TM - 1) / TM);
     const char* e = std::getenv("PSD_SFB_F32_TILE");   // tuning aid: 1 or 2
     const int bn = e ? std::atoi(e) : (tiles128 < 2 * int64_t(cus) ? 1 : 2);
-    if (bn == 1) return launch_f32<1>(U, ldu, V, ldv, W, Mom, N, M, K, lr, mu, st);
-    return launch_f32<2>(U, ldu, V, ldv, W, Mom, N, M, K, lr, mu, st);
+    if (bn == 1) return launch_f32<1>(U, ldu, V, ldv, W, Mom, N, M, K, lr, mu, wd, st);
+    return launch_f32<2>(U, ldu, V, ldv, W, Mom, N, M, K, lr, mu, wd, st);
 }
 
 }  // namespace psd

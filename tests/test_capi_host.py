@@ -111,44 +111,47 @@ def test_device_entry_points_reject_bad_arguments_before_launching():
     assert L.psd_pack_factors(pp, good, good, psd.BF16, U, 12, V, 8, None) == psd.E_INVALID    # ld*2 % 16
     assert L.psd_pack_factors(pp, good, good, psd.F32, _fake(0x10004), 8, V, 8, None) == psd.E_INVALID
     # sfb
-    assert L.psd_sync_fc_sfb(pp, psd.F32, U, 8, V, 8, None, Mom, 0.1, 0.9, None) == psd.E_NULL
-    assert L.psd_sync_fc_sfb(pp, 9, U, 8, V, 8, W, Mom, 0.1, 0.9, None) == psd.E_INVALID
-    assert L.psd_sync_fc_sfb(pp, psd.F32, U, 8, V, 8, W, W, 0.1, 0.9, None) == psd.E_INVALID
-    assert L.psd_sync_fc_sfb(pp, psd.F32, U, 8, V, 8, _fake(0x30008), Mom, 0.1, 0.9, None) == psd.E_INVALID
-    assert L.psd_sync_fc_sfb(pp, psd.BF16, U, 8, V, 7, W, Mom, 0.1, 0.9, None) == psd.E_INVALID
+    assert L.psd_sync_fc_sfb(pp, psd.F32, U, 8, V, 8, None, Mom, 0.1, 0.9, 0.0, None) == psd.E_NULL
+    assert L.psd_sync_fc_sfb(pp, 9, U, 8, V, 8, W, Mom, 0.1, 0.9, 0.0, None) == psd.E_INVALID
+    assert L.psd_sync_fc_sfb(pp, psd.F32, U, 8, V, 8, W, W, 0.1, 0.9, 0.0, None) == psd.E_INVALID
+    assert L.psd_sync_fc_sfb(pp, psd.F32, U, 8, V, 8, _fake(0x30008), Mom, 0.1, 0.9, 0.0, None) == psd.E_INVALID
+    assert L.psd_sync_fc_sfb(pp, psd.BF16, U, 8, V, 7, W, Mom, 0.1, 0.9, 0.0, None) == psd.E_INVALID
     bad = psd.Plan()
     ctypes.memmove(ctypes.byref(bad), ctypes.byref(plan), ctypes.sizeof(plan))
     bad.P = 0
-    assert L.psd_sync_fc_sfb(ctypes.byref(bad), psd.F32, U, 8, V, 8, W, Mom, 0.1, 0.9, None) == psd.E_INVALID
+    assert L.psd_sync_fc_sfb(ctypes.byref(bad), psd.F32, U, 8, V, 8, W, Mom, 0.1, 0.9, 0.0, None) == psd.E_INVALID
     # dense
-    assert L.psd_sync_dense_ps(16, 2, None, W, Mom, 0.1, 0.9, 1, None) == psd.E_NULL
-    assert L.psd_sync_dense_ps(16, 2, null, W, Mom, 0.1, 0.9, 1, None) == psd.E_NULL
-    assert L.psd_sync_dense_ps(16, 0, good, W, Mom, 0.1, 0.9, 1, None) == psd.E_INVALID
-    assert L.psd_sync_dense_ps(16, 65, good, W, Mom, 0.1, 0.9, 1, None) == psd.E_INVALID
-    assert L.psd_sync_dense_ps(16, 2, good, W, Mom, 0.1, 0.9, 17, None) == psd.E_INVALID     # S > n
-    assert L.psd_sync_dense_ps(16, 2, good, W, Mom, 0.1, 0.9, 0, None) == psd.E_INVALID
-    assert L.psd_sync_dense_ps(-1, 2, good, W, Mom, 0.1, 0.9, 1, None) == psd.E_INVALID
-    assert L.psd_sync_dense_ps(16, 2, odd, W, Mom, 0.1, 0.9, 1, None) == psd.E_INVALID
-    assert L.psd_sync_dense_ps(0, 2, good, W, Mom, 0.1, 0.9, 1, None) == psd.OK              # empty layer: no-op
+    assert L.psd_sync_dense_ps(16, 2, None, W, Mom, 0.1, 0.9, 0.0, 1, None) == psd.E_NULL
+    assert L.psd_sync_dense_ps(16, 2, null, W, Mom, 0.1, 0.9, 0.0, 1, None) == psd.E_NULL
+    assert L.psd_sync_dense_ps(16, 0, good, W, Mom, 0.1, 0.9, 0.0, 1, None) == psd.E_INVALID
+    assert L.psd_sync_dense_ps(16, 65, good, W, Mom, 0.1, 0.9, 0.0, 1, None) == psd.E_INVALID
+    assert L.psd_sync_dense_ps(16, 2, good, W, Mom, 0.1, 0.9, 0.0, 17, None) == psd.E_INVALID     # S > n
+    assert L.psd_sync_dense_ps(16, 2, good, W, Mom, 0.1, 0.9, 0.0, 0, None) == psd.E_INVALID
+    assert L.psd_sync_dense_ps(-1, 2, good, W, Mom, 0.1, 0.9, 0.0, 1, None) == psd.E_INVALID
+    assert L.psd_sync_dense_ps(16, 2, odd, W, Mom, 0.1, 0.9, 0.0, 1, None) == psd.E_INVALID
+    assert L.psd_sync_dense_ps(0, 2, good, W, Mom, 0.1, 0.9, 0.0, 1, None) == psd.OK              # empty layer: no-op
+    assert L.psd_sync_dense_ps(16, 2, good, W, Mom, 0.1, 0.9, -1e-4, 1, None) == psd.E_INVALID     # negative weight decay
+    assert L.psd_sync_dense_ps(16, 2, good, W, Mom, 0.1, 0.9, float('nan'), 1, None) == psd.E_INVALID
+    assert L.psd_sync_fc_sfb(pp, psd.F32, U, 8, V, 8, W, Mom, 0.1, 0.9, -1.0, None) == psd.E_INVALID
     # multi
     seg = (psd.DenseSegment * 1)()
     seg[0].n, seg[0].P, seg[0].S = 16, 2, 1
     seg[0].G = ctypes.cast(good, ctypes.POINTER(f32p))
     seg[0].W, seg[0].Mom = ctypes.cast(0x30000, f32p), ctypes.cast(0x40000, f32p)
-    assert L.psd_sync_dense_ps_multi(0, seg, 0.1, 0.9, None) == psd.E_INVALID
-    assert L.psd_sync_dense_ps_multi(17, seg, 0.1, 0.9, None) == psd.E_INVALID
-    assert L.psd_sync_dense_ps_multi(1, None, 0.1, 0.9, None) == psd.E_NULL
+    assert L.psd_sync_dense_ps_multi(0, seg, 0.1, 0.9, 0.0, None) == psd.E_INVALID
+    assert L.psd_sync_dense_ps_multi(17, seg, 0.1, 0.9, 0.0, None) == psd.E_INVALID
+    assert L.psd_sync_dense_ps_multi(1, None, 0.1, 0.9, 0.0, None) == psd.E_NULL
     seg[0].P = 17
-    assert L.psd_sync_dense_ps_multi(1, seg, 0.1, 0.9, None) == psd.E_INVALID
+    assert L.psd_sync_dense_ps_multi(1, seg, 0.1, 0.9, 0.0, None) == psd.E_INVALID
     seg[0].P, seg[0].n = 2, 0
-    assert L.psd_sync_dense_ps_multi(1, seg, 0.1, 0.9, None) == psd.OK                       # nothing to do
+    assert L.psd_sync_dense_ps_multi(1, seg, 0.1, 0.9, 0.0, None) == psd.OK                       # nothing to do
     # iteration
-    assert L.psd_sync_iteration(1, None, 0.1, 0.9, 0) == psd.E_NULL
+    assert L.psd_sync_iteration(1, None, 0.1, 0.9, 0.0, 0) == psd.E_NULL
     task = (psd.LayerTask * 1)()
     task[0].plan = psd.plan_layer(psd.LAYER_CONV, 8, 8, 2, 2)
-    assert L.psd_sync_iteration(0, task, 0.1, 0.9, 0) == psd.E_INVALID
-    assert L.psd_sync_iteration(1, task, 0.1, 0.9, 7) == psd.E_INVALID
-    assert L.psd_sync_iteration(1, task, 0.1, 0.9, 0) == psd.E_UNSUPPORTED                   # PS route without G
+    assert L.psd_sync_iteration(0, task, 0.1, 0.9, 0.0, 0) == psd.E_INVALID
+    assert L.psd_sync_iteration(1, task, 0.1, 0.9, 0.0, 7) == psd.E_INVALID
+    assert L.psd_sync_iteration(1, task, 0.1, 0.9, 0.0, 0) == psd.E_UNSUPPORTED                   # PS route without G
     for s in (0, -1, -2, -3, -4, -5, -99):
         assert L.psd_status_string(s)
 
@@ -163,11 +166,11 @@ def test_sizes_beyond_what_the_kernels_index_are_refused_before_launching():
     assert L.psd_pack_factors(ctypes.byref(plan), ptrs, ptrs, psd.F32, U, 8, V, 8, None) == psd.E_UNSUPPORTED
     # the reconstruct kernels use 32-bit byte offsets into each stacked factor matrix
     plan = psd.plan_layer(psd.LAYER_FC, 8, 2 ** 21, 256, 8)          # U: 2048 x 2^21 bf16 = 8.6 GB
-    assert L.psd_sync_fc_sfb(ctypes.byref(plan), psd.BF16, U, 2 ** 21, V, 8, W, Mom, 0.1, 0.9, None) == psd.E_UNSUPPORTED
-    assert L.psd_sync_fc_sfb(ctypes.byref(plan), psd.F32, U, 2 ** 21, V, 8, W, Mom, 0.1, 0.9, None) == psd.E_UNSUPPORTED
+    assert L.psd_sync_fc_sfb(ctypes.byref(plan), psd.BF16, U, 2 ** 21, V, 8, W, Mom, 0.1, 0.9, 0.0, None) == psd.E_UNSUPPORTED
+    assert L.psd_sync_fc_sfb(ctypes.byref(plan), psd.F32, U, 2 ** 21, V, 8, W, Mom, 0.1, 0.9, 0.0, None) == psd.E_UNSUPPORTED
     # M, N, K beyond 2^31 are invalid for the device entry points (the plan itself is fine)
     plan = psd.plan_layer(psd.LAYER_FC, 2 ** 31, 8, 1, 1)
-    assert L.psd_sync_fc_sfb(ctypes.byref(plan), psd.F32, U, 8, V, 2 ** 31, W, Mom, 0.1, 0.9, None) == psd.E_INVALID
+    assert L.psd_sync_fc_sfb(ctypes.byref(plan), psd.F32, U, 8, V, 2 ** 31, W, Mom, 0.1, 0.9, 0.0, None) == psd.E_INVALID
 
 
 def test_binding_fails_loudly_without_the_library(monkeypatch):

@@ -199,6 +199,39 @@ def test_sfb_f32_both_tile_shapes_bit_exact(tile, monkeypatch):
     assert np.array_equal(Mg, Mr) and np.array_equal(Wg, Wr)
 
 
+@pytest.mark.parametrize("dtype", [psd.F32, psd.BF16])
+def test_weight_decay_bit_exact_on_both_routes(dtype):
+    # wd, lr, mu powers of two and integer data: every intermediate is exact in fp32
+    d = inputs.fc_layer_integer(M=260, N=141, B=6, P=4, seed=71)
+    plan, U, ldu, V, ldv = run_pack(d, dtype)
+    W, Mom = dev(d["W"]), dev(d["Mom"])
+    psd.sync_fc_sfb(plan, dtype, U, ldu, V, ldv, W, Mom, 0.25, 0.5, wd=0.5)
+    torch.cuda.synchronize()
+    Uo, Vo = orc.pack_factors(d["delta"], d["act"])
+    Wr, Mr = orc.sync_fc_sfb(Uo, Vo, d["W"], d["Mom"], 0.25, 0.5, wd=0.5)
+    assert np.array_equal(Mom.cpu().numpy(), Mr) and np.array_equal(W.cpu().numpy(), Wr)
+    if dtype == psd.F32:
+        g = inputs.dense_layer_integer(70001, 5, seed=72)
+        W, Mom = dev(g["W"]), dev(g["Mom"])
+        psd.sync_dense_ps([dev(x) for x in g["G"]], W, Mom, 0.25, 0.5, 7, wd=0.5)
+        torch.cuda.synchronize()
+        Wr, Mr = orc.sync_dense_ps(g["G"], g["W"], g["Mom"], 0.25, 0.5, 7, wd=0.5)
+        assert np.array_equal(Mom.cpu().numpy(), Mr) and np.array_equal(W.cpu().numpy(), Wr)
+
+
+def test_weight_decay_gaussian_within_tolerance():
+    d = inputs.fc_layer(M=1000, N=500, B=32, P=4, seed=73, mom_std=1e-4)
+    for dtype, name in ((psd.F32, "f32"), (psd.BF16, "bf16")):
+        plan, U, ldu, V, ldv = run_pack(d, dtype)
+        W, Mom = dev(d["W"]), dev(d["Mom"])
+        psd.sync_fc_sfb(plan, dtype, U, ldu, V, ldv, W, Mom, inputs.LR, inputs.MU, wd=5e-4)
+        torch.cuda.synchronize()
+        Uo, Vo = orc.pack_factors(d["delta"], d["act"], name)
+        Wr, Mr = orc.sync_fc_sfb(Uo, Vo, d["W"], d["Mom"], inputs.LR, inputs.MU, wd=5e-4)
+        e = three_errors(d["W"], W.cpu().numpy(), Mom.cpu().numpy(), Wr, Mr)
+        assert max(e) <= TOL_F32, (name, e)
+
+
 def test_sfb_single_sample_is_exact_outer_product():
     d = inputs.fc_layer(M=200, N=150, B=1, P=1, seed=5)
     d["Mom"][:] = 0

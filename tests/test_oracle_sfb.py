@@ -198,3 +198,45 @@ def test_update_uses_fp32_rate_values_and_rounds_once():
     W2, Mom2 = orc.momentum_update(dW, W, Mom, 0.01, 0.9)
     mom = float(mu32) * 0.5 + float(lr32) * 3.0
     assert Mom2[0] == np.float32(mom) and W2[0] == np.float32(1.0 - mom)
+
+
+# ---------------------------------------------------------------------------------------
+# weight decay: the "regularisation" half of Lambda (Section 3.3)
+# ---------------------------------------------------------------------------------------
+def test_weight_decay_alone_shrinks_the_weights():
+    W = np.array([[8.0, -4.0], [2.0, 64.0]], np.float32)
+    Z = np.zeros((2, 2))
+    W2, Mom2 = orc.momentum_update(Z, W, np.zeros_like(W), lr=0.25, mu=0.0, wd=0.5)
+    assert np.array_equal(Mom2, 0.125 * W) and np.array_equal(W2, 0.875 * W)      # (1 - lr*wd) W
+    # wd = 0 is the plain update
+    a = orc.momentum_update(Z + 3, W, W, 0.25, 0.5)
+    b = orc.momentum_update(Z + 3, W, W, 0.25, 0.5, 0.0)
+    assert np.array_equal(a[0], b[0]) and np.array_equal(a[1], b[1])
+
+
+def test_weight_decay_is_the_gradient_of_the_l2_penalty():
+    # loss + wd/2 ||W||^2 has gradient dW + wd W: check against central differences
+    P, B, M, N, A, W, y = _tiny_problem(seed=8)
+    wd = 0.25
+    total = lambda Wx: _softmax_ce_loss(Wx, A, y) + 0.5 * wd * (Wx ** 2).sum()
+    fd = np.zeros_like(W)
+    h = 1e-6
+    for n in range(N):
+        for m in range(M):
+            Wp, Wm = W.copy(), W.copy()
+            Wp[n, m] += h
+            Wm[n, m] -= h
+            fd[n, m] = (total(Wp) - total(Wm)) / (2 * h)
+    delta = _softmax_ce_delta(W, A, y).astype(np.float32)
+    W2, Mom2 = orc.sync_fc_sfb(delta, A.astype(np.float32), W.astype(np.float32),
+                               np.zeros_like(W, dtype=np.float32), lr=1.0, mu=0.0, wd=wd)
+    assert np.allclose(Mom2, fd, rtol=0, atol=5e-6)        # Mom' = lr * (dW + wd W) with lr = 1
+    assert total(W2.astype(np.float64) + 0.99 * fd) < total(W)   # W2 = W - fd; a 1 % step along it lowers the penalised loss
+
+
+def test_dense_route_applies_the_same_weight_decay():
+    d = inputs.dense_layer_integer(n=257, P=3, seed=14)
+    g = np.sum(np.stack(d["G"]).astype(np.int64), axis=0)
+    W2, Mom2 = orc.sync_dense_ps(d["G"], d["W"], d["Mom"], lr=0.25, mu=0.5, S=4, wd=0.5)
+    want_m = 0.5 * d["Mom"] + 0.25 * (g + 0.5 * d["W"])
+    assert np.array_equal(Mom2, want_m) and np.array_equal(W2, d["W"] - want_m)
