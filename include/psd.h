@@ -107,6 +107,15 @@ psd_status psd_sync_fc_sfb(const psd_plan* plan, int32_t factor_dtype,
                            const void* U, int64_t ldu, const void* V, int64_t ldv,
                            float* W, float* Mom, float lr, float mu, float wd, void* stream);
 
+/* Bias of an FC layer under SFB.  For z = W a + b the per-sample gradient w.r.t. b is the error
+ * vector itself (the chain rule behind Eq. 5), so with the stacked errors U of the layer
+ *     db[n] = sum_{k<K} U[k][n] ;  mom_bias <- mu*mom_bias + lr*(db + wd*bias) ;  bias <- bias - mom_bias.
+ * No extra communication: U is what SFB already delivered (the paper's volumes count weights
+ * only, Table 3).  U [dev] K x ldu as written by psd_pack_factors; bias, mom_bias [dev] N fp32,
+ * in place, 16-byte aligned.  fp32 accumulation, 16 interleaved partial sums per column. */
+psd_status psd_sync_fc_bias(const psd_plan* plan, int32_t factor_dtype, const void* U, int64_t ldu,
+                            float* bias, float* mom_bias, float lr, float mu, float wd, void* stream);
+
 /* Parameter-server route (Algorithm 1 master node; Algorithm 3 non-FC branch): for every
  * key i of every shard, g = sum_{p<P} G[p][i] (summed in p order, fp32), then the same
  * update (momentum mu, step lr, weight decay wd) on W[i], Mom[i].

@@ -168,3 +168,16 @@ void orc_dense_ps(const float* const* G, int64_t P, int64_t n, int64_t S,
         }
     }
 }
+
+/* ---- bias gradient ---------------------------------------------------------------------
+ * For z = W a + b the per-sample gradient w.r.t. b is the error vector (the chain rule that
+ * gives Eq. 5 for W), so db[n] = sum over all K stacked samples of U[k][n], in float64.
+ */
+void orc_bias_grad(const float* U, int64_t K, int64_t N, double* db)
+{
+    for (int64_t n = 0; n < N; ++n) {
+        double acc = 0.0;
+        for (int64_t k = 0; k < K; ++k) acc += (double)U[k * N + n];
+        db[n] = acc;
+    }
+}

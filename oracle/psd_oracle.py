@@ -22,7 +22,8 @@ Readings of the paper used here (each is also listed in the design notes):
 Pins (tests/test_oracle_*.py): the three communication volumes and two ratios printed in
 Section 4.3.1; finite-difference gradients of a tiny FC layer; K=1 outer product; rank
 bound; linearity; row-permutation invariance; numpy float64 matmul; closed forms of the
-update; torch's CPU bf16 cast; brute-force shard cover; SFB path == PS path.
+update; torch's CPU bf16 cast; brute-force shard cover; SFB path == PS path; bias gradient
+against finite differences and numpy's column sum.
 Parity unpinned: none.
 """
 from __future__ import annotations
@@ -68,6 +69,8 @@ def lib():
         L.orc_rebuild_samples.argtypes = [f32p, f32p, i64, i64, i64, i64p, i64p, i64, f64p]
         L.orc_update.argtypes = [f64p, f32p, f32p, ctypes.c_float, ctypes.c_float, ctypes.c_float, i64]
         L.orc_shard_range.argtypes = [i64, i64, i64, i64p, i64p]
+        L.orc_bias_grad.argtypes = [f32p, i64, i64, f64p]
+        L.orc_bias_grad.restype = None
         L.orc_dense_ps.argtypes = [ctypes.POINTER(f32p), i64, i64, i64, f32p, f32p,
                                    ctypes.c_float, ctypes.c_float, ctypes.c_float]
         for fn in (L.orc_bf16_round_array, L.orc_bf16_widen_array, L.orc_rebuild,
@@ -234,6 +237,21 @@ def momentum_update(dW, W, Mom, lr, mu, wd=0.0):
 def sync_fc_sfb(U, V, W, Mom, lr, mu, wd=0.0):
     """Alg. 3 SFB branch on one worker: rebuild from all stacked factors, then update."""
     return momentum_update(rebuild(U, V), W, Mom, lr, mu, wd)
+
+
+def bias_grad(U):
+    """db (N, float64) = sum_k U[k]: gradient of the loss w.r.t. the bias of z = W a + b."""
+    U = _factor_values(U)
+    K, N = U.shape
+    db = np.empty(N, dtype=np.float64)
+    lib().orc_bias_grad(U.ctypes.data_as(ctypes.POINTER(ctypes.c_float)), K, N,
+                        db.ctypes.data_as(ctypes.POINTER(ctypes.c_double)))
+    return db
+
+
+def sync_fc_bias(U, bias, mom_bias, lr, mu, wd=0.0):
+    """Bias of an FC layer under SFB: column sums of the stacked errors, then the same update."""
+    return momentum_update(bias_grad(U), bias, mom_bias, lr, mu, wd)
 
 
 def sync_dense_ps(G, W, Mom, lr, mu, S=1, wd=0.0):

@@ -53,11 +53,18 @@ def fc_config(psd, inputs, torch, dev, cfg_id, dtype_name=None, working_set_mb=6
         pack(i)
         sfb(i)
 
+    bias_sets = [(torch.zeros(N, device=dev), torch.zeros(N, device=dev)) for _ in range(n_sets)]
+
+    def bias(i):
+        s = sets[i]
+        psd.sync_fc_bias(plan, dtype, s["U"], s["ldu"], bias_sets[i][0], bias_sets[i][1], inputs.LR, inputs.MU)
+
     for i in range(n_sets):
         pack(i)
     t_pack = _time_ms(torch, pack, n_sets)
     t_sfb = _time_ms(torch, sfb, n_sets)
     t_both = _time_ms(torch, both, n_sets)
+    t_bias = _time_ms(torch, bias, n_sets)
     flops = 2 * N * M * K
     bytes_sfb = 16 * N * M + K * (M + N) * es
     bytes_pack = K * (M + N) * (4 + es)
@@ -67,7 +74,8 @@ def fc_config(psd, inputs, torch, dev, cfg_id, dtype_name=None, working_set_mb=6
                 sfb_frac_mfma=round(flops / t_sfb / 1e9 / PEAK_TF[dtype_name], 4),
                 sfb_GBps=round(bytes_sfb / t_sfb / 1e6, 1), sfb_frac_hbm=round(bytes_sfb / t_sfb / 1e6 / PEAK_HBM_GBS, 4),
                 pack_ms=round(t_pack, 5), pack_GBps=round(bytes_pack / t_pack / 1e6, 1),
-                pack_plus_sfb_ms=round(t_both, 5), pack_plus_sfb_TFLOPs=round(flops / t_both / 1e9, 2))
+                pack_plus_sfb_ms=round(t_both, 5), pack_plus_sfb_TFLOPs=round(flops / t_both / 1e9, 2),
+                bias_ms=round(t_bias, 5), bias_GBps=round((K * N * es + 16 * N) / t_bias / 1e6, 1))
 
 
 def dense_sweep(psd, inputs, torch, dev, sizes=(2332704, 16777216, 37748736, 89460736), P=8, S=8):

@@ -74,6 +74,9 @@ SIGNATURES = {
     "psd_sync_fc_sfb": (ctypes.c_int32, [ctypes.POINTER(Plan), ctypes.c_int32, ctypes.c_void_p, ctypes.c_int64,
                                          ctypes.c_void_p, ctypes.c_int64, ctypes.c_void_p, ctypes.c_void_p,
                                          ctypes.c_float, ctypes.c_float, ctypes.c_float, ctypes.c_void_p]),
+    "psd_sync_fc_bias": (ctypes.c_int32, [ctypes.POINTER(Plan), ctypes.c_int32, ctypes.c_void_p, ctypes.c_int64,
+                                          ctypes.c_void_p, ctypes.c_void_p, ctypes.c_float, ctypes.c_float,
+                                          ctypes.c_float, ctypes.c_void_p]),
     "psd_sync_dense_ps": (ctypes.c_int32, [ctypes.c_int64, ctypes.c_int32, _f32pp, ctypes.c_void_p, ctypes.c_void_p,
                                            ctypes.c_float, ctypes.c_float, ctypes.c_float, ctypes.c_int32,
                                            ctypes.c_void_p]),
@@ -185,6 +188,14 @@ def sync_fc_sfb(plan, factor_dtype, U, ldu, V, ldv, W, Mom, lr, mu, stream=None,
     mp = _dev_ptr(Mom, torch.float32, plan.N * plan.M, "Mom")
     _check(lib().psd_sync_fc_sfb(ctypes.byref(plan), factor_dtype, up, ldu, vp, ldv, wp, mp, lr, mu, wd,
                                  _stream_handle(stream)), "psd_sync_fc_sfb")
+
+
+def sync_fc_bias(plan, factor_dtype, U, ldu, bias, mom_bias, lr, mu, stream=None, wd=0.0):
+    up = _dev_ptr(U, _FACTOR_TORCH.get(factor_dtype, ()), plan.K * ldu, "U")
+    bp = _dev_ptr(bias, torch.float32, plan.N, "bias")
+    mp = _dev_ptr(mom_bias, torch.float32, plan.N, "mom_bias")
+    _check(lib().psd_sync_fc_bias(ctypes.byref(plan), factor_dtype, up, ldu, bp, mp, lr, mu, wd,
+                                  _stream_handle(stream)), "psd_sync_fc_bias")
 
 
 def sync_dense_ps(G, W, Mom, lr, mu, S, stream=None, wd=0.0):

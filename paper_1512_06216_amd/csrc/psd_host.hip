@@ -145,6 +145,18 @@ psd_status psd_sync_fc_sfb(const psd_plan* plan, int32_t factor_dtype, const voi
                            plan->N, plan->M, K, lr, mu, wd, st);
 }
 
+psd_status psd_sync_fc_bias(const psd_plan* plan, int32_t factor_dtype, const void* U, int64_t ldu, float* bias,
+                            float* mom_bias, float lr, float mu, float wd, void* stream)
+{
+    if (!plan || !U || !bias || !mom_bias) return PSD_E_NULL;
+    if (factor_dtype != PSD_F32 && factor_dtype != PSD_BF16) return PSD_E_INVALID;
+    if (!(wd >= 0.0f)) return PSD_E_INVALID;
+    if (!valid_plan_sizes(plan) || !valid_ld(ldu, plan->N, factor_dtype)) return PSD_E_INVALID;
+    if (!aligned16(U) || !aligned16(bias) || !aligned16(mom_bias) || bias == mom_bias) return PSD_E_INVALID;
+    return launch_bias(U, ldu, factor_dtype, plan->N, plan->P * plan->B, bias, mom_bias, lr, mu, wd,
+                       static_cast<hipStream_t>(stream));
+}
+
 static psd_status check_dense(int64_t n, int32_t P, int32_t maxP, const float* const* G, const float* W,
                               const float* Mom, int32_t S)
 {

@@ -60,4 +60,7 @@ psd_status launch_sfb_f32(const float* U, int64_t ldu, const float* V, int64_t l
 psd_status launch_sfb_bf16(const uint16_t* U, int64_t ldu, const uint16_t* V, int64_t ldv, float* W, float* Mom,
                            int64_t N, int64_t M, int64_t K, float lr, float mu, float wd, hipStream_t st);
 
+psd_status launch_bias(const void* U, int64_t ldu, int32_t dtype, int64_t N, int64_t K, float* bias, float* mom,
+                       float lr, float mu, float wd, hipStream_t st);
+
 }  // namespace psd

@@ -120,6 +120,12 @@ def test_device_entry_points_reject_bad_arguments_before_launching():
     ctypes.memmove(ctypes.byref(bad), ctypes.byref(plan), ctypes.sizeof(plan))
     bad.P = 0
     assert L.psd_sync_fc_sfb(ctypes.byref(bad), psd.F32, U, 8, V, 8, W, Mom, 0.1, 0.9, 0.0, None) == psd.E_INVALID
+    # bias
+    assert L.psd_sync_fc_bias(pp, psd.F32, U, 8, None, Mom, 0.1, 0.9, 0.0, None) == psd.E_NULL
+    assert L.psd_sync_fc_bias(pp, psd.F32, U, 8, W, W, 0.1, 0.9, 0.0, None) == psd.E_INVALID
+    assert L.psd_sync_fc_bias(pp, psd.F32, U, 6, W, Mom, 0.1, 0.9, 0.0, None) == psd.E_INVALID       # ld < N
+    assert L.psd_sync_fc_bias(pp, 3, U, 8, W, Mom, 0.1, 0.9, 0.0, None) == psd.E_INVALID
+    assert L.psd_sync_fc_bias(pp, psd.BF16, U, 8, W, Mom, 0.1, 0.9, -0.5, None) == psd.E_INVALID
     # dense
     assert L.psd_sync_dense_ps(16, 2, None, W, Mom, 0.1, 0.9, 0.0, 1, None) == psd.E_NULL
     assert L.psd_sync_dense_ps(16, 2, null, W, Mom, 0.1, 0.9, 0.0, 1, None) == psd.E_NULL

@@ -330,6 +330,43 @@ def test_sfb_second_workload_shapes_sampled(M, N, B, P, dtype):
     assert np.array_equal(Wg, d["W"] - Mg)                # every weight updated exactly once
 
 
+@pytest.mark.parametrize("M,N,B,P", [(16, 1, 1, 1), (40, 127, 3, 5), (64, 1000, 16, 8), (8, 21841, 4, 2), (32, 300, 1, 37)])
+@pytest.mark.parametrize("dtype", [psd.F32, psd.BF16])
+def test_bias_integer_errors_bit_exact(M, N, B, P, dtype):
+    d = inputs.fc_layer_integer(M, N, B, P, seed=N + B)
+    plan, U, ldu, V, ldv = run_pack(d, dtype)
+    rng = np.random.default_rng(N)
+    b0 = rng.integers(-64, 65, size=N).astype(np.float32)
+    m0 = rng.integers(-8, 9, size=N).astype(np.float32)
+    bias, mom = dev(b0), dev(m0)
+    psd.sync_fc_bias(plan, dtype, U, ldu, bias, mom, 0.25, 0.5, wd=0.5)
+    torch.cuda.synchronize()
+    Uo, _ = orc.pack_factors(d["delta"], d["act"])
+    br, mr = orc.sync_fc_bias(Uo, b0, m0, 0.25, 0.5, wd=0.5)
+    assert np.array_equal(mom.cpu().numpy(), mr) and np.array_equal(bias.cpu().numpy(), br)
+
+
+@pytest.mark.parametrize("cfg,dtype", [(2, psd.F32), (3, psd.BF16), (4, psd.BF16)])
+def test_bias_full_size_configs(cfg, dtype):
+    d = inputs.fc_config(cfg)
+    plan, U, ldu, V, ldv = run_pack(d, dtype)
+    N = d["N"]
+    b0 = (np.random.default_rng(cfg).standard_normal(N) * 0.1).astype(np.float32)
+    bias, mom = dev(b0), dev(np.zeros(N, np.float32))
+    psd.sync_fc_bias(plan, dtype, U, ldu, bias, mom, inputs.LR, inputs.MU)
+    torch.cuda.synchronize()
+    Uo, _ = orc.pack_factors(d["delta"], d["act"], "f32" if dtype == psd.F32 else "bf16")
+    br, mr = orc.sync_fc_bias(Uo, b0, np.zeros(N, np.float32), inputs.LR, inputs.MU)
+    if cfg == 4:
+        # softmax errors: every column sum is a difference of nearly equal numbers (the classes'
+        # probabilities against the rare one-hot hits), so compare absolutely, scaled by sum |U|
+        scale = np.float64(np.float32(inputs.LR)) * np.abs(orc.bf16_widen(Uo).astype(np.float64)).sum(axis=0)
+        assert np.all(np.abs(mom.cpu().numpy().astype(np.float64) - mr) <= 1e-6 * scale + 1e-12)
+    else:
+        assert orc.rel_frob(mom.cpu().numpy(), mr) <= TOL_F32
+    assert orc.rel_frob(bias.cpu().numpy(), br) <= TOL_F32
+
+
 def test_sfb_equals_ps_route_on_the_same_gradients():
     # Section 4.3.1: factors reconstruct the gradient exactly, so both routes agree
     d = inputs.fc_layer_integer(M=300, N=200, B=4, P=3, seed=31)
