@@ -32,7 +32,7 @@ PEAK_MFMA_TFLOPS = {"bf16": 2500.0, "f32": 157.3}
 # HBM bytes per launch of the dominant kernel measured with rocprofv3 --pmc (FETCH_SIZE and
 # WRITE_SIZE runs, scaled by a copy kernel of known size); filled in from the committed
 # profile summaries, None where not measured.
-MEASURED_TRAFFIC_BYTES = {"bf16": 923_700_000, "f32": None}   # fc6 launch; profiles/bench_config5_bf16_hbm_traffic.txt
+MEASURED_TRAFFIC_BYTES = {"bf16": 922_900_000, "f32": None}   # fc6 launch; profiles/bench_config5_bf16_hbm_traffic.txt
 
 
 class HipEvents:

@@ -29,14 +29,38 @@ bias_kernel(const void* __restrict__ Uv, int64_t ldu, int N, int K, float* __res
     if (c0 < ldu) {                                                  // ldu is even: c0 + 1 < ldu as well
         if constexpr (BF16) {
             const uint16_t* U = static_cast<const uint16_t*>(Uv);
-            for (int k = wave; k < K; k += kWaves) {
+            int k = wave;
+            for (; k + 7 * kWaves < K; k += 8 * kWaves) {            // 8 independent loads in flight per lane
+                uint32_t v[8];
+#pragma unroll
+                for (int u = 0; u < 8; ++u)
+                    v[u] = *reinterpret_cast<const uint32_t*>(U + int64_t(k + u * kWaves) * ldu + c0);
+#pragma unroll
+                for (int u = 0; u < 8; ++u) {
+                    s0 += __uint_as_float(v[u] << 16);               // bf16 -> fp32 is a shift
+                    s1 += __uint_as_float(v[u] & 0xffff0000u);
+                }
+            }
+            for (; k < K; k += kWaves) {
                 const uint32_t v = *reinterpret_cast<const uint32_t*>(U + int64_t(k) * ldu + c0);
-                s0 += __uint_as_float(v << 16);                      // bf16 -> fp32 is a shift
+                s0 += __uint_as_float(v << 16);
                 s1 += __uint_as_float(v & 0xffff0000u);
             }
         } else {
             const float* U = static_cast<const float*>(Uv);
-            for (int k = wave; k < K; k += kWaves) {
+            int k = wave;
+            for (; k + 7 * kWaves < K; k += 8 * kWaves) {
+                float2 v[8];
+#pragma unroll
+                for (int u = 0; u < 8; ++u)
+                    v[u] = *reinterpret_cast<const float2*>(U + int64_t(k + u * kWaves) * ldu + c0);
+#pragma unroll
+                for (int u = 0; u < 8; ++u) {
+                    s0 += v[u].x;
+                    s1 += v[u].y;
+                }
+            }
+            for (; k < K; k += kWaves) {
                 const float2 v = *reinterpret_cast<const float2*>(U + int64_t(k) * ldu + c0);
                 s0 += v.x;
                 s1 += v.y;
