@@ -121,6 +121,29 @@ def cpu_baseline(layers, fc_dtype_name, lr, mu):
     return time.perf_counter() - t0, orc.num_threads()
 
 
+def cpu_baseline_configs(inputs):
+    """The oracle on the single-layer FC configurations: reconstruct + update, all host threads, and
+    one thread for the two small ones (part of the cpu_baseline leg; only run with --extras)."""
+    from oracle import psd_oracle as orc
+    orc.lib()
+    all_threads = orc.num_threads()
+    out = []
+    for cfg in (1, 2, 3, 4):
+        d = inputs.fc_config(cfg)
+        name = d["factor_dtype"]
+        U, V = orc.pack_factors(d["delta"], d["act"], name)
+        flops = 2.0 * d["N"] * d["M"] * d["P"] * d["B"]
+        for threads in ([all_threads, 1] if cfg <= 2 else [all_threads]):
+            orc.set_num_threads(threads)
+            t0 = time.perf_counter()
+            orc.sync_fc_sfb(U, V, d["W"], d["Mom"], inputs.LR, inputs.MU)
+            dt = time.perf_counter() - t0
+            out.append({"config": cfg, "factor_dtype": name, "threads": threads, "ms": round(dt * 1e3, 2),
+                        "GFLOPs": round(flops / dt / 1e9, 2)})
+        orc.set_num_threads(all_threads)
+    return out
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -271,6 +294,8 @@ def main():
     if args.extras:
         from paper_1512_06216_amd import bench_extras
         extras = bench_extras.run(psd, inputs, torch, dev)
+        if not args.no_cpu_baseline:
+            extras["cpu_baseline_configs"] = cpu_baseline_configs(inputs)
         with open(args.extras, "w") as f:
             json.dump(extras, f, indent=1)
         out["extras_file"] = args.extras

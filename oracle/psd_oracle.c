@@ -181,3 +181,13 @@ void orc_bias_grad(const float* U, int64_t K, int64_t N, double* db)
         db[n] = acc;
     }
 }
+
+/* thread count used by the timed cpu_baseline runs (no arithmetic) */
+void orc_set_num_threads(int n)
+{
+#ifdef _OPENMP
+    if (n > 0) omp_set_num_threads(n);
+#else
+    (void)n;
+#endif
+}

@@ -84,6 +84,11 @@ def num_threads():
     return int(lib().orc_num_threads())
 
 
+def set_num_threads(n):
+    """OpenMP threads used by the C loops from now on (for the timed baseline runs)."""
+    lib().orc_set_num_threads(ctypes.c_int(int(n)))
+
+
 def _f32(a):
     a = np.ascontiguousarray(a, dtype=np.float32)
     return a, a.ctypes.data_as(ctypes.POINTER(ctypes.c_float))

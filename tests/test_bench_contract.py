@@ -16,8 +16,8 @@ def test_more_than_one_gpu_is_refused_with_a_message():
 def test_bench_imports_the_oracle_only_inside_the_cpu_baseline_leg():
     src = open(os.path.join(ROOT, "bench.py")).read()
     lines = [l for l in src.splitlines() if ("import" in l and "oracle" in l)]
-    assert lines == ["    from oracle import psd_oracle as orc"]
-    head = src.split("def cpu_baseline", 1)[0]
+    assert lines == ["    from oracle import psd_oracle as orc"] * 2      # cpu_baseline and cpu_baseline_configs
+    head = src.split("def layer_work", 1)[0]
     assert "from oracle" not in head and "import oracle" not in head
 
 
