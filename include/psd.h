@@ -155,6 +155,10 @@ typedef struct psd_layer_task {
                                   NULL for an FC layer that is routed to SFB / SF_PS) */
     float* W; float* Mom;      /* [dev] N x M fp32 */
     void* stream;              /* the stream this layer's work is enqueued on */
+    void* ev_ready;            /* optional hipEvent_t (or NULL): the layer's stream waits for it before any
+                                  of the layer's work starts -- "the gradient of this layer exists"
+                                  (Algorithm 2: a layer is synchronised as soon as backpropagation has
+                                  produced its gradient, while lower layers are still computing) */
     void* ev_begin;            /* optional hipEvent_t (or NULL) recorded on `stream` right before */
     void* ev_end;              /* ... and right after the layer's reconstruct+update or
                                   sum+update kernel (factor packing lies outside the pair) */

@@ -101,10 +101,92 @@ def dense_sweep(psd, inputs, torch, dev, sizes=(2332704, 16777216, 37748736, 894
     return out
 
 
+# Forward multiply-adds per image of the 8 AlexNet layers (conv1..conv5, fc6..fc8); their sum matches the
+# 1 352 M conv / 117 M FC FLOPs per image of the paper's Table 3 to within the rounding of that table when a
+# multiply-add counts as one FLOP.
+ALEXNET_MFLOP = [105.4, 223.9, 149.5, 112.1, 74.8, 37.7, 16.8, 4.1]
+
+
+def dwbp_overlap(psd, inputs, torch, dev, iters=10):
+    """Iteration time when the synchronisation of a layer starts as soon as its gradient exists
+    (Algorithm 2) against starting all synchronisation after the whole backward pass.
+
+    Backpropagation itself is outside this build, so each layer's backward work is a stand-in: a bf16
+    matmul on a 'backward' stream sized to twice the layer's forward FLOPs at batch 256 (data and weight
+    gradients).  Only the schedule is the subject here; the stand-in computes nothing that is used."""
+    import ctypes
+    hip = ctypes.CDLL("libamdhip64.so")
+    hip.hipEventCreate.argtypes = [ctypes.POINTER(ctypes.c_void_p)]
+    hip.hipEventRecord.argtypes = [ctypes.c_void_p, ctypes.c_void_p]
+    layers = inputs.cnn_iteration()
+    streams = [torch.cuda.Stream(device=dev) for _ in layers]
+    backward = torch.cuda.Stream(device=dev)
+    tasks, standins = [], []
+    for L, st, mflop in zip(layers, streams, ALEXNET_MFLOP):
+        ev = ctypes.c_void_p()
+        assert hip.hipEventCreate(ctypes.byref(ev)) == 0
+        if L["kind"] == "conv":
+            plan = psd.plan_layer(psd.LAYER_CONV, L["n"], 1, inputs.CNN_B, L["P"])
+            t = dict(plan=plan, G=[torch.from_numpy(g).to(dev) for g in L["G"]], S=inputs.CNN_S,
+                     W=torch.from_numpy(L["W"]).to(dev), Mom=torch.from_numpy(L["Mom"]).to(dev), stream=st)
+        else:
+            plan = psd.plan_layer(psd.LAYER_FC, L["M"], L["N"], L["B"], L["P"])
+            U, ldu, V, ldv = psd.alloc_factors(plan, psd.BF16, dev)
+            t = dict(plan=plan, factor_dtype=psd.BF16, delta=[torch.from_numpy(x).to(dev) for x in L["delta"]],
+                     act=[torch.from_numpy(x).to(dev) for x in L["act"]], U=U, ldu=ldu, V=V, ldv=ldv,
+                     W=torch.from_numpy(L["W"]).to(dev), Mom=torch.from_numpy(L["Mom"]).to(dev), stream=st)
+        t["_ev"] = ev.value
+        tasks.append(t)
+        # 2 * forward FLOPs * 256 images as one square-ish matmul: 2*n^3 = 2 * 2 * mflop*1e6 * 256
+        n = int(round((2.0 * mflop * 1e6 * 256) ** (1.0 / 3.0) / 64.0)) * 64
+        standins.append((torch.randn(n, n, device=dev, dtype=torch.bfloat16) * 0.01,
+                         torch.randn(n, n, device=dev, dtype=torch.bfloat16) * 0.01))
+
+    def backward_pass(record):
+        with torch.cuda.stream(backward):
+            for j in range(len(layers) - 1, -1, -1):          # top layer first
+                a, b = standins[j]
+                torch.matmul(a, b)
+                if record:
+                    assert hip.hipEventRecord(tasks[j]["_ev"], ctypes.c_void_p(backward.cuda_stream)) == 0
+
+    it_plain = psd.Iteration(tasks)
+    it_events = psd.Iteration([dict(t, ev_ready=t["_ev"]) for t in tasks])
+
+    def one(mode):
+        if mode == "backward_only":
+            backward_pass(False)
+        elif mode == "sync_only":
+            it_plain.run(inputs.LR, inputs.MU)
+        elif mode == "sync_after_backward":
+            backward_pass(False)
+            torch.cuda.synchronize()                           # all gradients exist, then synchronise
+            it_plain.run(inputs.LR, inputs.MU)
+        else:                                                  # wait-free: per-layer events
+            backward_pass(True)
+            it_events.run(inputs.LR, inputs.MU)
+
+    import time
+    out = {}
+    for mode in ("backward_only", "sync_only", "sync_after_backward", "wait_free"):
+        for _ in range(3):
+            one(mode)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(iters):
+            one(mode)
+            torch.cuda.synchronize()                           # one iteration at a time: no cross-iteration overlap
+        out[mode + "_ms"] = round((time.perf_counter() - t0) / iters * 1e3, 4)
+    out["note"] = ("backward = bf16 matmul stand-ins of 2x the AlexNet forward FLOPs per layer at batch 256; "
+                   "sync = the 8-layer config-5 synchronisation, bf16 factors")
+    return out
+
+
 def run(psd, inputs, torch, dev):
     res = {"fc": [], "dense_sweep": None}
     for cfg, dt in [(1, "f32"), (2, "f32"), (2, "bf16"), (3, "bf16"), (3, "f32"), (4, "bf16")]:
         res["fc"].append(fc_config(psd, inputs, torch, dev, cfg, dt))
         torch.cuda.empty_cache()
     res["dense_sweep"] = dense_sweep(psd, inputs, torch, dev)
+    res["dwbp_overlap"] = dwbp_overlap(psd, inputs, torch, dev)
     return res

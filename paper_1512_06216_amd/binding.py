@@ -50,7 +50,7 @@ class LayerTask(ctypes.Structure):
                 ("delta_p", _f32pp), ("act_p", _f32pp),
                 ("U", ctypes.c_void_p), ("ldu", ctypes.c_int64), ("V", ctypes.c_void_p), ("ldv", ctypes.c_int64),
                 ("G", _f32pp), ("W", _f32p), ("Mom", _f32p), ("stream", ctypes.c_void_p),
-                ("ev_begin", ctypes.c_void_p), ("ev_end", ctypes.c_void_p)]
+                ("ev_ready", ctypes.c_void_p), ("ev_begin", ctypes.c_void_p), ("ev_end", ctypes.c_void_p)]
 
 
 class PsdError(RuntimeError):
@@ -228,7 +228,8 @@ class Iteration:
 
     Each layer is a dict: FC  -> plan, factor_dtype, delta, act, U, ldu, V, ldv, W, Mom, stream
                          conv -> plan, G, S, W, Mom, stream
-    plus optional ev_begin / ev_end (raw hipEvent_t handles as ints).
+    plus optional ev_ready (the layer's stream waits for it first) and ev_begin / ev_end (recorded
+    around the layer's sync kernel); all raw hipEvent_t handles as ints.
     Building it does no device work; run() makes the single library call.
     """
 
@@ -243,6 +244,7 @@ class Iteration:
             t.W = ctypes.cast(_dev_ptr(L["W"], torch.float32, n, "W"), _f32p)
             t.Mom = ctypes.cast(_dev_ptr(L["Mom"], torch.float32, n, "Mom"), _f32p)
             t.stream = _stream_handle(L.get("stream"))
+            t.ev_ready = L.get("ev_ready")
             t.ev_begin, t.ev_end = L.get("ev_begin"), L.get("ev_end")   # raw hipEvent_t handles or None
             t.S = L.get("S", 1)
             t.factor_dtype = L.get("factor_dtype", F32)

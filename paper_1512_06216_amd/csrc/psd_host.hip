@@ -223,6 +223,7 @@ psd_status psd_sync_iteration(int32_t L, const psd_layer_task* layers, float lr,
         const psd_layer_task& t = layers[l];
         const int32_t route = rule == PSD_RULE_ALG3 ? t.plan.route_alg3 : t.plan.route_vs_dense;
         hipStream_t st = static_cast<hipStream_t>(t.stream);
+        if (t.ev_ready) PSD_HIP_TRY(hipStreamWaitEvent(st, static_cast<hipEvent_t>(t.ev_ready), 0));
         psd_status r;
         if (route == PSD_ROUTE_PS_DENSE) {
             if (!t.G) return PSD_E_UNSUPPORTED;   // route needs dense gradient copies

@@ -27,7 +27,7 @@ def test_library_exports_every_declared_symbol():
 def test_struct_layouts_match_the_header():
     assert ctypes.sizeof(psd.Plan) == 4 * 8 + 4 * 4 + 3 * 8
     assert ctypes.sizeof(psd.DenseSegment) == 8 + 4 + 4 + 3 * 8
-    assert ctypes.sizeof(psd.LayerTask) == ctypes.sizeof(psd.Plan) + 8 + 2 * 8 + 4 * 8 + 8 + 2 * 8 + 8 + 2 * 8
+    assert ctypes.sizeof(psd.LayerTask) == ctypes.sizeof(psd.Plan) + 8 + 2 * 8 + 4 * 8 + 8 + 2 * 8 + 8 + 3 * 8
 
 
 GRID = list(itertools.product([1, 3, 128, 256, 1000, 4096, 9216], [1, 2, 128, 1000, 4096, 21841],

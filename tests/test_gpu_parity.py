@@ -455,6 +455,56 @@ def test_iteration_full_size_in_the_benchmark_configuration():
         assert max(e) <= TOL_F32, (L["name"], e)
 
 
+def test_iteration_waits_for_the_layers_gradient_event():
+    """Algorithm 2: a layer is synchronised as soon as its gradient exists.  The factors are written by
+    a 'backward' stream only after a long stretch of other work; the layer's stream must wait for the
+    event that marks them ready (without the wait it would read the zeros the buffers start with)."""
+    import ctypes
+    hip = ctypes.CDLL("libamdhip64.so")
+    hip.hipEventCreate.argtypes = [ctypes.POINTER(ctypes.c_void_p)]
+    hip.hipEventRecord.argtypes = [ctypes.c_void_p, ctypes.c_void_p]
+    hip.hipEventDestroy.argtypes = [ctypes.c_void_p]
+    d = inputs.fc_layer(M=512, N=384, B=16, P=4, seed=41)
+    g = inputs.dense_layer(50000, 4, seed=42)
+    plan = psd.plan_layer(psd.LAYER_FC, d["M"], d["N"], d["B"], d["P"])
+    pconv = psd.plan_layer(psd.LAYER_CONV, g["n"], 1, d["B"], g["P"])
+    U, ldu, V, ldv = psd.alloc_factors(plan, psd.BF16, DEV)
+    delta = [torch.zeros_like(dev(x)) for x in d["delta"]]
+    act = [torch.zeros_like(dev(x)) for x in d["act"]]
+    G = [torch.zeros_like(dev(x)) for x in g["G"]]
+    src_delta, src_act, src_G = [dev(x) for x in d["delta"]], [dev(x) for x in d["act"]], [dev(x) for x in g["G"]]
+    W, Mom, Wc, Mc = dev(d["W"]), dev(d["Mom"]), dev(g["W"]), dev(g["Mom"])
+    backward = torch.cuda.Stream(device=DEV)
+    s_fc, s_conv = torch.cuda.Stream(device=DEV), torch.cuda.Stream(device=DEV)
+    ev_fc, ev_conv = ctypes.c_void_p(), ctypes.c_void_p()
+    assert hip.hipEventCreate(ctypes.byref(ev_fc)) == 0 and hip.hipEventCreate(ctypes.byref(ev_conv)) == 0
+    big = torch.randn(4096, 4096, device=DEV)
+    torch.cuda.synchronize()
+    with torch.cuda.stream(backward):
+        for _ in range(20):                       # stand-in for the rest of backpropagation (tens of ms)
+            big = (big @ big) * 1e-3
+        for dst, src in zip(delta + act, src_delta + src_act):
+            dst.copy_(src)
+        assert hip.hipEventRecord(ev_fc, ctypes.c_void_p(backward.cuda_stream)) == 0      # top layer ready first
+        for _ in range(5):
+            big = (big @ big) * 1e-3
+        for dst, src in zip(G, src_G):
+            dst.copy_(src)
+        assert hip.hipEventRecord(ev_conv, ctypes.c_void_p(backward.cuda_stream)) == 0
+    tasks = [dict(plan=pconv, G=G, S=8, W=Wc, Mom=Mc, stream=s_conv, ev_ready=ev_conv.value),
+             dict(plan=plan, factor_dtype=psd.BF16, delta=delta, act=act, U=U, ldu=ldu, V=V, ldv=ldv, W=W, Mom=Mom,
+                  stream=s_fc, ev_ready=ev_fc.value)]
+    psd.Iteration(tasks).run(inputs.LR, inputs.MU, psd.RULE_ALG3)      # issued while 'backward' is still busy
+    torch.cuda.synchronize()
+    Uo, Vo = orc.pack_factors(d["delta"], d["act"], "bf16")
+    Wr, Mr = orc.sync_fc_sfb(Uo, Vo, d["W"], d["Mom"], inputs.LR, inputs.MU)
+    assert max(three_errors(d["W"], W.cpu().numpy(), Mom.cpu().numpy(), Wr, Mr)) <= TOL_F32
+    Wr, Mr = orc.sync_dense_ps(g["G"], g["W"], g["Mom"], inputs.LR, inputs.MU, 8)
+    assert max(three_errors(g["W"], Wc.cpu().numpy(), Mc.cpu().numpy(), Wr, Mr)) <= TOL_F32
+    hip.hipEventDestroy(ev_fc)
+    hip.hipEventDestroy(ev_conv)
+
+
 def test_iteration_routes_follow_the_plan():
     # fc8-shaped layer at P=8, B=256: Algorithm 3 says SF_PS, the prose rule says SFB; both
     # run the reconstruction.  A layer whose route is PS_DENSE but has no dense copies is refused.
