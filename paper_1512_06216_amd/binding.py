@@ -12,7 +12,7 @@ import os
 import torch
 
 _PKG = os.path.dirname(os.path.abspath(__file__))
-LIB_PATH = os.path.join(_PKG, os.environ.get("PSD_LIB_NAME", "libpsd.so"))
+LIB_PATH = os.path.join(_PKG, "libpsd.so")
 
 OK, E_INVALID, E_NULL, E_UNSUPPORTED, E_OVERFLOW, E_HIP = 0, -1, -2, -3, -4, -5
 LAYER_CONV, LAYER_FC = 0, 1
