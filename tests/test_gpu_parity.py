@@ -232,6 +232,50 @@ def test_weight_decay_gaussian_within_tolerance():
         assert max(e) <= TOL_F32, (name, e)
 
 
+def _random_shapes(count, seed):
+    rng = np.random.default_rng(seed)
+    out = []
+    for _ in range(count):
+        P = int(rng.integers(1, 10))
+        B = int(rng.integers(1, 40))
+        out.append((int(rng.integers(1, 700)), int(rng.integers(1, 700)), B, P))
+    return out
+
+
+@pytest.mark.parametrize("dtype", [psd.F32, psd.BF16])
+def test_sfb_random_shapes_bit_exact(dtype):
+    # 24 seeded random layer shapes (any width, any K tail) with integer data: pack, reconstruct,
+    # update and the bias path must all equal the oracle bit for bit
+    for (M, N, B, P) in _random_shapes(24, seed=2024):
+        d = inputs.fc_layer_integer(M, N, B, P, seed=M * 1000 + N)
+        plan, U, ldu, V, ldv = run_pack(d, dtype)
+        W, Mom = dev(d["W"]), dev(d["Mom"])
+        psd.sync_fc_sfb(plan, dtype, U, ldu, V, ldv, W, Mom, 0.25, 0.5, wd=0.25)
+        b0 = np.arange(N, dtype=np.float32) - N // 2
+        bias, mb = dev(b0), dev(np.zeros(N, np.float32))
+        psd.sync_fc_bias(plan, dtype, U, ldu, bias, mb, 0.25, 0.5)
+        torch.cuda.synchronize()
+        Uo, Vo = orc.pack_factors(d["delta"], d["act"])
+        Wr, Mr = orc.sync_fc_sfb(Uo, Vo, d["W"], d["Mom"], 0.25, 0.5, wd=0.25)
+        assert np.array_equal(Mom.cpu().numpy(), Mr) and np.array_equal(W.cpu().numpy(), Wr), (M, N, B, P)
+        br, mr = orc.sync_fc_bias(Uo, b0, np.zeros(N, np.float32), 0.25, 0.5)
+        assert np.array_equal(bias.cpu().numpy(), br) and np.array_equal(mb.cpu().numpy(), mr), (M, N, B, P)
+
+
+def test_dense_random_sizes_bit_exact():
+    rng = np.random.default_rng(77)
+    for _ in range(24):
+        n = int(rng.integers(1, 300000))
+        P = int(rng.integers(1, 20))
+        S = int(rng.integers(1, min(n, 40) + 1))
+        d = inputs.dense_layer_integer(n, P, seed=n)
+        W, Mom = dev(d["W"]), dev(d["Mom"])
+        psd.sync_dense_ps([dev(g) for g in d["G"]], W, Mom, 0.125, 0.5, S, wd=0.5)
+        torch.cuda.synchronize()
+        Wr, Mr = orc.sync_dense_ps(d["G"], d["W"], d["Mom"], 0.125, 0.5, S, wd=0.5)
+        assert np.array_equal(W.cpu().numpy(), Wr) and np.array_equal(Mom.cpu().numpy(), Mr), (n, P, S)
+
+
 def test_sfb_single_sample_is_exact_outer_product():
     d = inputs.fc_layer(M=200, N=150, B=1, P=1, seed=5)
     d["Mom"][:] = 0
