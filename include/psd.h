@@ -174,6 +174,15 @@ typedef struct psd_layer_task {
 psd_status psd_sync_iteration(int32_t L, const psd_layer_task* layers, float lr, float mu, float wd,
                               int32_t rule);
 
+/* Tuning / test hook (not part of the method): pins the workgroup tile the reconstruction kernels
+ * use instead of letting the library pick one from the layer shape.  Process-wide, takes effect on
+ * the next launch; value -1 restores the automatic choice; any other value outside the listed range is
+ * refused with PSD_E_INVALID and changes nothing.  Results never depend on the tile (only speed does).
+ *   PSD_TUNE_SFB_BF16_TILE: 0 = 128 x 256, 1 = 128 x 192, 2 = 128 x 128 (rows n x columns m of W)
+ *   PSD_TUNE_SFB_F32_TILE:  1 = 64 x 128,  2 = 128 x 128 */
+enum { PSD_TUNE_SFB_BF16_TILE = 0, PSD_TUNE_SFB_F32_TILE = 1, PSD_TUNE_COUNT_ = 2 };
+psd_status psd_tune_set(int32_t knob, int32_t value);
+
 const char* psd_status_string(psd_status s);
 /* hipError_t value of the most recent failing HIP call on this thread (0 if none). */
 int32_t psd_last_hip_error(void);

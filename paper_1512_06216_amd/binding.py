@@ -19,6 +19,7 @@ LAYER_CONV, LAYER_FC = 0, 1
 ROUTE_PS_DENSE, ROUTE_SFB, ROUTE_SF_PS = 0, 1, 2
 RULE_ALG3, RULE_SFB_VS_DENSE = 0, 1
 F32, BF16 = 0, 1
+TUNE_SFB_BF16_TILE, TUNE_SFB_F32_TILE = 0, 1
 ROUTE_NAMES = {ROUTE_PS_DENSE: "PS_DENSE", ROUTE_SFB: "SFB", ROUTE_SF_PS: "SF_PS"}
 MAX_WORKERS, MAX_MULTI_SEGMENTS, MAX_MULTI_WORKERS = 64, 16, 16
 
@@ -84,6 +85,7 @@ SIGNATURES = {
                                                  ctypes.c_float, ctypes.c_float, ctypes.c_void_p]),
     "psd_sync_iteration": (ctypes.c_int32, [ctypes.c_int32, ctypes.POINTER(LayerTask), ctypes.c_float,
                                             ctypes.c_float, ctypes.c_float, ctypes.c_int32]),
+    "psd_tune_set": (ctypes.c_int32, [ctypes.c_int32, ctypes.c_int32]),
     "psd_status_string": (ctypes.c_char_p, [ctypes.c_int32]),
     "psd_last_hip_error": (ctypes.c_int32, []),
     "psd_version": (ctypes.c_int32, []),
@@ -146,6 +148,11 @@ def plan_layer(kind, M, N, B, P):
     p = Plan()
     _check(lib().psd_plan_layer(kind, M, N, B, P, ctypes.byref(p)), "psd_plan_layer")
     return p
+
+
+def tune_set(knob, value):
+    """Pins (or with -1 releases) a kernel tile choice; tuning / test hook."""
+    _check(lib().psd_tune_set(knob, value), "psd_tune_set")
 
 
 def shard_range(n, S, s):

@@ -10,6 +10,7 @@
 // wavefronts owns 128 adjacent columns: lane l of every wavefront reads columns 2l, 2l+1 of
 // one row with a single 4-byte (bf16) or 8-byte (fp32) load, wavefront w takes rows
 // k = w, w+16, ..., and the 16 partial sums meet in LDS, added in wavefront order.
+#include "psd_device.h"
 #include "psd_internal.h"
 
 namespace psd {
@@ -77,9 +78,9 @@ bias_kernel(const void* __restrict__ Uv, int64_t ldu, int N, int K, float* __res
 #pragma unroll
             for (int w = 1; w < kWaves; ++w) d += part[w][threadIdx.x];
             float b = bias[n], m = mom[n];
-            m = __fmaf_rn(mu, m, lr * __fmaf_rn(wd, b, d));
+            upd(d, b, m, lr, mu, wd);
             mom[n] = m;
-            bias[n] = b - m;
+            bias[n] = b;
         }
     }
 }

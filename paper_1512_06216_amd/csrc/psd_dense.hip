@@ -11,6 +11,7 @@
 // memory and the whole launch walks the key space once, shard after shard.  Giving each
 // XCD its own shard instead (workgroup g -> shard g % S) was measured 6% slower at S = 8 and
 // 10% slower at S = 64: eight far-apart streams per array collide on HBM channels.
+#include "psd_device.h"
 #include "psd_internal.h"
 
 namespace psd {
@@ -34,12 +35,6 @@ __device__ __forceinline__ float4 ld_stream(const float* p)
 {
     const f32x4 v = __builtin_nontemporal_load(reinterpret_cast<const f32x4*>(p));
     return make_float4(v.x, v.y, v.z, v.w);
-}
-
-__device__ __forceinline__ void update1(float g, float& w, float& mom, float lr, float mu, float wd)
-{
-    mom = __fmaf_rn(mu, mom, lr * __fmaf_rn(wd, w, g));   // wd = 0 leaves g unchanged
-    w = w - mom;
 }
 
 // keys [lo, hi) of one layer; PC > 0: number of copies known at compile time
@@ -84,10 +79,10 @@ __device__ __forceinline__ void dense_span(const float* const* __restrict__ G, i
 #pragma unroll
     for (int u = 0; u < kDenseUnroll; ++u) {
         if (idx[u] < hi4) {
-            update1(acc[u].x, w[u].x, m[u].x, lr, mu, wd);
-            update1(acc[u].y, w[u].y, m[u].y, lr, mu, wd);
-            update1(acc[u].z, w[u].z, m[u].z, lr, mu, wd);
-            update1(acc[u].w, w[u].w, m[u].w, lr, mu, wd);
+            upd(acc[u].x, w[u].x, m[u].x, lr, mu, wd);
+            upd(acc[u].y, w[u].y, m[u].y, lr, mu, wd);
+            upd(acc[u].z, w[u].z, m[u].z, lr, mu, wd);
+            upd(acc[u].w, w[u].w, m[u].w, lr, mu, wd);
             *reinterpret_cast<float4*>(Mom + idx[u]) = m[u];
             *reinterpret_cast<float4*>(W + idx[u]) = w[u];
         }
@@ -100,7 +95,7 @@ __device__ __forceinline__ void dense_span(const float* const* __restrict__ G, i
         float g = G[0][i];
         for (int p = 1; p < nP; ++p) g += G[p][i];
         float wv = W[i], mv = Mom[i];
-        update1(g, wv, mv, lr, mu, wd);
+        upd(g, wv, mv, lr, mu, wd);
         Mom[i] = mv;
         W[i] = wv;
     }

@@ -1,5 +1,6 @@
 // Host side of libpsd: route selection, shard ranges, argument validation and the
 // per-iteration issue order.  No device code here.
+#include <atomic>
 #include "psd_internal.h"
 
 namespace psd {
@@ -8,6 +9,23 @@ psd_status hip_failed(hipError_t e)
 {
     g_last_hip_error = static_cast<int32_t>(e);
     return PSD_E_HIP;
+}
+
+static std::atomic<int> g_tune[PSD_TUNE_COUNT_] = {{-1}, {-1}};
+int tune_value(int knob) { return knob >= 0 && knob < PSD_TUNE_COUNT_ ? g_tune[knob].load(std::memory_order_relaxed) : -1; }
+
+int device_cu_count()
+{
+    constexpr int kMaxDev = 64;
+    static std::atomic<int> cached[kMaxDev];          // 0 = not queried yet
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDev) return 256;
+    int cus = cached[dev].load(std::memory_order_relaxed);
+    if (cus == 0) {
+        if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || cus < 1) cus = 256;
+        cached[dev].store(cus, std::memory_order_relaxed);
+    }
+    return cus;
 }
 }  // namespace psd
 
@@ -37,7 +55,17 @@ bool valid_ld(int64_t ld, int64_t cols, int32_t dtype)
 
 extern "C" {
 
-int32_t psd_version(void) { return 1; }
+int32_t psd_version(void) { return 2; }
+
+psd_status psd_tune_set(int32_t knob, int32_t value)
+{
+    if (knob < 0 || knob >= PSD_TUNE_COUNT_) return PSD_E_INVALID;
+    const int32_t limit = knob == PSD_TUNE_SFB_BF16_TILE ? 2 : 2;
+    const int32_t low = knob == PSD_TUNE_SFB_BF16_TILE ? 0 : 1;
+    if (value != -1 && (value < low || value > limit)) return PSD_E_INVALID;
+    g_tune[knob].store(value, std::memory_order_relaxed);
+    return PSD_OK;
+}
 
 int32_t psd_last_hip_error(void) { return g_last_hip_error; }
 

@@ -17,6 +17,11 @@ psd_status hip_failed(hipError_t e);
 
 inline bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 
+// Value of a psd_tune_set() knob; -1 = let the library choose.
+int tune_value(int knob);
+// Compute units of the current device (queried once per device, then cached).
+int device_cu_count();
+
 // ---- launchers (one per kernel family); arguments are already validated ----------------
 struct DenseSeg {
     const float* G[PSD_MAX_MULTI_WORKERS];

@@ -20,7 +20,7 @@
 // accumulator rows a lane owns are four adjacent m of one W row; the epilogue turns each
 // block through LDS so that W and Mom move in 16-byte accesses, 128 contiguous bytes per row.
 #include <atomic>
-#include <cstdlib>
+#include "psd_device.h"
 #include "psd_internal.h"
 
 namespace psd {
@@ -29,7 +29,6 @@ namespace {
 typedef float f32x16 __attribute__((ext_vector_type(16)));
 typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
-typedef int i32x4 __attribute__((ext_vector_type(4)));
 typedef __attribute__((address_space(3))) bf16x4 lds_bf16x4;
 
 constexpr int KT = 32;         // k rows per LDS stage (two MFMA k-steps of 16)
@@ -55,55 +54,9 @@ struct Cfg {
     static_assert(NSTAGE >= 3, "the pipeline keeps at least one stage in flight beyond the one being awaited");
 };
 
-// global -> LDS, 16 bytes per lane: lane i's chunk lands at lds_addr + 16*i.  A lane whose
-// offset is at or past the descriptor's size writes zeros.
-__device__ __forceinline__ void dma_b128(uint32_t lds_addr_uniform, uint32_t voff, i32x4 rsrc)
-{
-    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tbuffer_load_dwordx4 %1, %2, 0 offen lds"
-                 :
-                 : "s"(lds_addr_uniform), "v"(voff), "s"(rsrc)
-                 : "memory");
-}
-
-template <int N>
-__device__ __forceinline__ void wait_vmcnt()
-{
-    asm volatile("s_waitcnt vmcnt(%0)" : : "n"(N) : "memory");
-}
-
-__device__ __forceinline__ i32x4 factor_rsrc(const uint16_t* X, uint32_t bytes)
-{
-    const uint64_t a = reinterpret_cast<uint64_t>(X);
-    i32x4 r;
-    r.x = static_cast<int>(a & 0xffffffffu);
-    r.y = static_cast<int>((a >> 32) & 0xffffu);      // stride 0: raw buffer, byte-granular range check
-    r.z = static_cast<int>(bytes);
-    r.w = 0x00020000;
-    return r;
-}
-
 __device__ __forceinline__ bf16x4 read_tr(uint32_t lds_addr)
 {
     return __builtin_amdgcn_ds_read_tr16_b64_v4bf16(reinterpret_cast<lds_bf16x4*>(lds_addr));
-}
-
-__device__ __forceinline__ void upd(float d, float& w, float& mo, float lr, float mu, float wd)
-{
-    mo = __fmaf_rn(mu, mo, lr * __fmaf_rn(wd, w, d));   // wd = 0 leaves d unchanged
-    w = w - mo;
-}
-
-// Scheduling pattern for one pipeline phase holding MF MFMAs and R LDS reads that do not depend
-// on each other: 1 MFMA, then its share of the reads, and so on.
-template <int R, int MF, int I = 0>
-__device__ __forceinline__ void interleave_groups()
-{
-    if constexpr (I < MF) {
-        __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);                    // one MFMA
-        constexpr int n = R * (I + 1) / MF - R * I / MF;
-        if constexpr (n > 0) __builtin_amdgcn_sched_group_barrier(0x100, n, 0);  // n DS reads
-        interleave_groups<R, MF, I + 1>();
-    }
 }
 
 template <class C>
@@ -137,7 +90,7 @@ sfb_bf16_kernel(const uint16_t* __restrict__ U, int64_t ldu, const uint16_t* __r
     // of rows, or row fragments for 384-byte rows), lane i carrying the chunk that belongs at
     // physical position i of that run.
     // physical chunk pc of row r holds logical chunk pc ^ ((r & 3) << 1)
-    const i32x4 rsrc_u = factor_rsrc(U, u_bytes), rsrc_v = factor_rsrc(V, v_bytes);
+    const i32x4 rsrc_u = raw_rsrc(U, u_bytes), rsrc_v = raw_rsrc(V, v_bytes);
     uint32_t voff_a[C::NI_A], voff_b[C::NI_B];
     {
         constexpr int LPR = C::RA / 16;              // 16-byte chunks per row
@@ -358,45 +311,34 @@ psd_status launch_cfg(const uint16_t* U, int64_t ldu, const uint16_t* V, int64_t
     return PSD_OK;
 }
 
-using Cfg256x256w4 = Cfg<2, 2, 4, 4, 4, 1>;   // 4 wavefronts of 128 x 128, 4 stages (128 KiB), one workgroup per CU
-using Cfg256x128w4 = Cfg<2, 2, 4, 2, 3, 2>;   // 4 wavefronts of 128 x 64, 3 stages (72 KiB), two workgroups per CU
 using Cfg128x256w4 = Cfg<2, 2, 2, 4, 3, 2>;   // 4 wavefronts of 64 x 128, 3 stages (72 KiB), two workgroups per CU
-using Cfg256x256w8 = Cfg<2, 4, 4, 2, 4, 2>;   // 8 wavefronts of 128 x 64, 4 stages (128 KiB), one workgroup per CU
-using Cfg128x128w4 = Cfg<2, 2, 2, 2, 4, 2>;   // small layers: more workgroups (64 KiB, two per CU)
 using Cfg128x192w4 = Cfg<2, 2, 2, 3, 4, 2>;   // 4 wavefronts of 64 x 96, 4 stages (80 KiB), two workgroups per CU
-// (0, 1 and 3 are never picked by the heuristic below; they stay selectable for tuning and are covered by the tests)
+using Cfg128x128w4 = Cfg<2, 2, 2, 2, 4, 2>;   // small layers: more workgroups (64 KiB, two per CU)
 
 }  // namespace
 
 psd_status launch_sfb_bf16(const uint16_t* U, int64_t ldu, const uint16_t* V, int64_t ldv, float* W, float* Mom,
                            int64_t N, int64_t M, int64_t K, float lr, float mu, float wd, hipStream_t st)
 {
-    // PSD_SFB_BF16_TILE overrides the tile choice (tuning aid): index into the switch below
-    const char* e = std::getenv("PSD_SFB_BF16_TILE");
-    int pick = e ? std::atoi(e) : -1;
+    int pick = tune_value(PSD_TUNE_SFB_BF16_TILE);
     if (pick < 0) {
         // Workgroups of one launch run in rounds of (CUs x workgroups per CU); a partly filled last
         // round costs as much as a full one.  Pick the tile whose rounds x tile area is smallest
         // (ties go to the larger tile; the 128 x 128 tile pays ~10% for its lower MFMA duty).
-        int dev = 0, cus = 256;
-        if (hipGetDevice(&dev) == hipSuccess) (void)hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev);
-        struct Cand { int id, tn, tm, per_cu, weight; };
-        const Cand cands[] = {{2, 128, 256, 2, 100}, {7, 128, 192, 2, 100}, {4, 128, 128, 2, 110}};
+        const int64_t slots = int64_t(device_cu_count()) * 2;
+        struct Cand { int id, tn, tm, weight; };
+        const Cand cands[] = {{0, 128, 256, 100}, {1, 128, 192, 100}, {2, 128, 128, 110}};
         int64_t best = -1;
         for (const Cand& c : cands) {
             const int64_t tiles = ((N + c.tn - 1) / c.tn) * ((M + c.tm - 1) / c.tm);
-            const int64_t slots = int64_t(cus) * c.per_cu;
             const int64_t cost = ((tiles + slots - 1) / slots) * c.tn * c.tm * c.weight;
             if (best < 0 || cost < best) { best = cost; pick = c.id; }
         }
     }
     switch (pick) {
-        case 0: return launch_cfg<Cfg256x256w4>(U, ldu, V, ldv, W, Mom, N, M, K, lr, mu, wd, st);
-        case 1: return launch_cfg<Cfg256x128w4>(U, ldu, V, ldv, W, Mom, N, M, K, lr, mu, wd, st);
-        case 2: return launch_cfg<Cfg128x256w4>(U, ldu, V, ldv, W, Mom, N, M, K, lr, mu, wd, st);
-        case 3: return launch_cfg<Cfg256x256w8>(U, ldu, V, ldv, W, Mom, N, M, K, lr, mu, wd, st);
-        case 4: return launch_cfg<Cfg128x128w4>(U, ldu, V, ldv, W, Mom, N, M, K, lr, mu, wd, st);
-        case 7: return launch_cfg<Cfg128x192w4>(U, ldu, V, ldv, W, Mom, N, M, K, lr, mu, wd, st);
+        case 0: return launch_cfg<Cfg128x256w4>(U, ldu, V, ldv, W, Mom, N, M, K, lr, mu, wd, st);
+        case 1: return launch_cfg<Cfg128x192w4>(U, ldu, V, ldv, W, Mom, N, M, K, lr, mu, wd, st);
+        case 2: return launch_cfg<Cfg128x128w4>(U, ldu, V, ldv, W, Mom, N, M, K, lr, mu, wd, st);
         default: return PSD_E_INVALID;
     }
 }

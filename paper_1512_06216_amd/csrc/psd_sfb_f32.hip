@@ -17,7 +17,7 @@
 // the buffer range check zero-fills the K tail.  A stage is 16 k rows = two half-stages of
 // 4 MFMA k-pairs; the operand reads of one half are issued before the MFMAs of the half before
 // and interleaved with them, and the workgroup barrier sits between the two halves.
-#include <cstdlib>
+#include "psd_device.h"
 #include "psd_internal.h"
 
 namespace psd {
@@ -25,58 +25,12 @@ namespace {
 
 typedef float f32x16 __attribute__((ext_vector_type(16)));
 
-typedef int i32x4 __attribute__((ext_vector_type(4)));
 typedef float f32x2 __attribute__((ext_vector_type(2)));
 
 constexpr int TM = 128;             // workgroup tile width (m)
 constexpr int KT = 16;              // k rows per LDS stage
 constexpr int THREADS = 256;
 constexpr int NSTAGE = 4;           // ring depth
-
-__device__ __forceinline__ void upd(float d, float& w, float& mo, float lr, float mu, float wd)
-{
-    mo = __fmaf_rn(mu, mo, lr * __fmaf_rn(wd, w, d));   // wd = 0 leaves d unchanged
-    w = w - mo;
-}
-
-// global -> LDS, 16 bytes per lane: lane i's chunk lands at lds_addr + 16*i; a lane whose
-// offset is at or past the descriptor's size writes zeros
-__device__ __forceinline__ void dma_b128(uint32_t lds_addr_uniform, uint32_t voff, i32x4 rsrc)
-{
-    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tbuffer_load_dwordx4 %1, %2, 0 offen lds"
-                 :
-                 : "s"(lds_addr_uniform), "v"(voff), "s"(rsrc)
-                 : "memory");
-}
-
-template <int N>
-__device__ __forceinline__ void wait_vmcnt()
-{
-    asm volatile("s_waitcnt vmcnt(%0)" : : "n"(N) : "memory");
-}
-
-__device__ __forceinline__ i32x4 factor_rsrc(const float* X, uint32_t bytes)
-{
-    const uint64_t a = reinterpret_cast<uint64_t>(X);
-    i32x4 r;
-    r.x = static_cast<int>(a & 0xffffffffu);
-    r.y = static_cast<int>((a >> 32) & 0xffffu);      // stride 0: raw buffer, byte-granular range check
-    r.z = static_cast<int>(bytes);
-    r.w = 0x00020000;
-    return r;
-}
-
-// 1 MFMA, then its share of the LDS reads of the next half-stage, and so on
-template <int R, int MF, int I = 0>
-__device__ __forceinline__ void interleave_groups()
-{
-    if constexpr (I < MF) {
-        __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
-        constexpr int n = R * (I + 1) / MF - R * I / MF;
-        if constexpr (n > 0) __builtin_amdgcn_sched_group_barrier(0x100, n, 0);
-        interleave_groups<R, MF, I + 1>();
-    }
-}
 
 // BN = MFMA blocks per wavefront along n: workgroup tile (64*BN) x 128, wavefront tile (32*BN) x 64.
 // BN = 2 is the default; BN = 1 doubles the number of workgroups for layers with few tiles.
@@ -103,7 +57,7 @@ sfb_f32_kernel(const float* __restrict__ U, int64_t ldu, const float* __restrict
     const int l32 = lane & 31, lhi = lane >> 5;
 
     // DMA plan: run j of this wavefront covers chunks f = (wave*NI + j)*64 + lane of the stage
-    const i32x4 rsrc_u = factor_rsrc(U, u_bytes), rsrc_v = factor_rsrc(V, v_bytes);
+    const i32x4 rsrc_u = raw_rsrc(U, u_bytes), rsrc_v = raw_rsrc(V, v_bytes);
     uint32_t voff_a[NI_A], voff_b[NI_B];
 #pragma unroll
     for (int j = 0; j < NI_A; ++j) {
@@ -250,11 +204,9 @@ psd_status launch_sfb_f32(const float* U, int64_t ldu, const float* V, int64_t l
 {
     // 128 x 128 tiles unless that leaves fewer than two workgroups per compute unit (one workgroup's
     // four wavefronts cannot hide LDS and barrier latency on their own)
-    int dev = 0, cus = 256;
-    if (hipGetDevice(&dev) == hipSuccess) (void)hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev);
     const int64_t tiles128 = ((N + 127) / 128) * ((M + TM - 1) / TM);
-    const char* e = std::getenv("PSD_SFB_F32_TILE");   // tuning aid: 1 or 2
-    const int bn = e ? std::atoi(e) : (tiles128 < 2 * int64_t(cus) ? 1 : 2);
+    const int forced = tune_value(PSD_TUNE_SFB_F32_TILE);
+    const int bn = forced == 1 || forced == 2 ? forced : (tiles128 < 2 * int64_t(device_cu_count()) ? 1 : 2);
     if (bn == 1) return launch_f32<1>(U, ldu, V, ldv, W, Mom, N, M, K, lr, mu, wd, st);
     return launch_f32<2>(U, ldu, V, ldv, W, Mom, N, M, K, lr, mu, wd, st);
 }

@@ -21,7 +21,7 @@ def test_library_exports_every_declared_symbol():
     L = psd.lib()
     for name in declared:
         assert getattr(L, name) is not None
-    assert L.psd_version() == 1
+    assert L.psd_version() == 2
 
 
 def test_struct_layouts_match_the_header():
@@ -184,3 +184,13 @@ def test_binding_fails_loudly_without_the_library(monkeypatch):
     monkeypatch.setattr(psd, "LIB_PATH", "/nonexistent/libpsd.so")
     with pytest.raises(RuntimeError, match="not built"):
         psd.plan_layer(psd.LAYER_FC, 4, 4, 4, 4)
+
+
+def test_tune_hook_accepts_listed_values_only():
+    L = psd.lib()
+    for knob, good, bad in ((psd.TUNE_SFB_BF16_TILE, (0, 1, 2, -1), (3, -2, 100)), (psd.TUNE_SFB_F32_TILE, (1, 2, -1), (0, 3))):
+        for v in good:
+            assert L.psd_tune_set(knob, v) == psd.OK
+        for v in bad:
+            assert L.psd_tune_set(knob, v) == psd.E_INVALID
+    assert L.psd_tune_set(2, 0) == psd.E_INVALID and L.psd_tune_set(-1, 0) == psd.E_INVALID

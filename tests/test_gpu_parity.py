@@ -177,12 +177,26 @@ def test_sfb_integer_factors_bit_exact(M, N, B, P, dtype):
     assert np.array_equal(Wg, Wr)
 
 
-@pytest.mark.parametrize("tile", [0, 1, 2, 3, 4, 7])
-def test_sfb_bf16_every_tile_shape_bit_exact(tile, monkeypatch):
-    # every kernel instantiation the tile heuristic can pick (and the tuning-only ones), on a shape
-    # with ragged tiles in both directions, a K tail, and more than one tile per direction
-    monkeypatch.setenv("PSD_SFB_BF16_TILE", str(tile))
-    d = inputs.fc_layer_integer(M=520, N=300, B=11, P=5, seed=tile + 50)
+@pytest.fixture
+def pinned_tile():
+    """Pins a kernel tile through the library's tuning hook and releases it afterwards."""
+    pinned = []
+
+    def pin(knob, value):
+        psd.tune_set(knob, value)
+        pinned.append(knob)
+    yield pin
+    for knob in pinned:
+        psd.tune_set(knob, -1)
+
+
+@pytest.mark.parametrize("tile", [0, 1, 2])
+@pytest.mark.parametrize("M,N,B,P", [(520, 300, 11, 5),       # ragged tiles both ways, K tail, K shorter than the row prefetch
+                                     (700, 260, 160, 9)])     # K = 1440: past the unrolled prefetch stages, ragged stage tail
+def test_sfb_bf16_every_tile_shape_bit_exact(tile, M, N, B, P, pinned_tile):
+    # every kernel instantiation the tile heuristic can pick (and the tuning-only one)
+    pinned_tile(psd.TUNE_SFB_BF16_TILE, tile)
+    d = inputs.fc_layer_integer(M=M, N=N, B=B, P=P, seed=tile + 50, amax=2 if B * P > 1000 else 3)
     Wg, Mg, _ = run_sfb(d, psd.BF16, 0.25, 0.5)
     U, V = orc.pack_factors(d["delta"], d["act"])
     Wr, Mr = orc.sync_fc_sfb(U, V, d["W"], d["Mom"], 0.25, 0.5)
@@ -190,8 +204,8 @@ def test_sfb_bf16_every_tile_shape_bit_exact(tile, monkeypatch):
 
 
 @pytest.mark.parametrize("tile", [1, 2])
-def test_sfb_f32_both_tile_shapes_bit_exact(tile, monkeypatch):
-    monkeypatch.setenv("PSD_SFB_F32_TILE", str(tile))
+def test_sfb_f32_both_tile_shapes_bit_exact(tile, pinned_tile):
+    pinned_tile(psd.TUNE_SFB_F32_TILE, tile)
     d = inputs.fc_layer_integer(M=391, N=203, B=7, P=3, seed=tile + 60)
     Wg, Mg, _ = run_sfb(d, psd.F32, 0.25, 0.5)
     U, V = orc.pack_factors(d["delta"], d["act"])
