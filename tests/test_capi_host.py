@@ -194,3 +194,19 @@ def test_tune_hook_accepts_listed_values_only():
         for v in bad:
             assert L.psd_tune_set(knob, v) == psd.E_INVALID
     assert L.psd_tune_set(2, 0) == psd.E_INVALID and L.psd_tune_set(-1, 0) == psd.E_INVALID
+
+
+def test_factor_matrices_past_the_32_bit_offset_reach_are_refused_on_the_host():
+    """The reconstruction kernels address each stacked factor matrix with 32-bit byte offsets.  A layer
+    whose U or V would be larger is refused with PSD_E_UNSUPPORTED during validation, before anything is
+    launched (the pointers below are never dereferenced)."""
+    L = psd.lib()
+    fake = ctypes.c_void_p(0x10000000)               # aligned, non-null, never touched
+    # VGG-16's first FC layer is fine even at fp32 (25088 x 2048 x 4 B = 205 MB) ...
+    # ... a 2^20-wide layer at K = 2048 is not (4 GiB of bf16, 8 GiB of fp32)
+    big = psd.plan_layer(psd.LAYER_FC, 1 << 20, 256, 256, 8)
+    for dtype in (psd.BF16, psd.F32):
+        ldu, ldv = psd.factor_ld(big.N, dtype), psd.factor_ld(big.M, dtype)
+        st = L.psd_sync_fc_sfb(ctypes.byref(big), dtype, fake, ldu, fake, ldv, fake, ctypes.c_void_p(0x20000000),
+                               0.01, 0.9, 0.0, None)
+        assert st == psd.E_UNSUPPORTED, (dtype, st)

@@ -327,65 +327,89 @@ def test_sfb_bf16_small_gaussian_both_bars():
     assert max(e) <= TOL_BF16_VS_F32, e
 
 
-def _sample_positions(N, M, count, seed):
-    rng = np.random.default_rng(seed)
-    idx_n = rng.integers(0, N, count)
-    idx_m = rng.integers(0, M, count)
-    # always include the corners and the last row / column (ragged tiles)
-    idx_n[:4] = [0, 0, N - 1, N - 1]
-    idx_m[:4] = [0, M - 1, 0, M - 1]
-    idx_n[4:4 + 64] = N - 1
-    idx_m[64 + 4:64 + 68] = M - 1
-    return idx_n, idx_m
+def _whole_matrix_checks(d, Wg, Mg, factor_name, lr, mu, tol_vs_unrounded=None):
+    """Whole-matrix comparison with the float64 oracle fed the very factor bits the kernel saw: the three
+    relative Frobenius errors, and every single element against the worst-case bound of an fp32 sum of
+    K products in any order (unit roundoff 2^-24, K + 4 roundings) plus the fp32 roundings of the update."""
+    U, V = orc.pack_factors(d["delta"], d["act"], factor_name)
+    Wr, Mr = orc.sync_fc_sfb(U, V, d["W"], d["Mom"], lr, mu)
+    e = three_errors(d["W"], Wg, Mg, Wr, Mr)
+    assert max(e) <= TOL_F32, e
+    K = U.shape[0]
+    Uv = orc.bf16_widen(U) if U.dtype == np.uint16 else U
+    Vv = orc.bf16_widen(V) if V.dtype == np.uint16 else V
+    mass = orc.rebuild(np.abs(Uv), np.abs(Vv))                       # sum_k |u||v| per element (float64)
+    u = 2.0 ** -24
+    bound_m = (K + 4) * u * np.float64(np.float32(lr)) * mass + 4 * u * np.abs(Mr.astype(np.float64)) + 1e-30
+    err_m = np.abs(Mg.astype(np.float64) - Mr.astype(np.float64))
+    bad = np.argwhere(err_m > bound_m)
+    assert bad.size == 0, (bad[:5], err_m[tuple(bad[0])], bound_m[tuple(bad[0])])
+    bound_w = bound_m + 4 * u * np.abs(Wr.astype(np.float64))
+    err_w = np.abs(Wg.astype(np.float64) - Wr.astype(np.float64))
+    bad = np.argwhere(err_w > bound_w)
+    assert bad.size == 0, (bad[:5], err_w[tuple(bad[0])], bound_w[tuple(bad[0])])
+    if tol_vs_unrounded is not None:
+        U32, V32 = orc.pack_factors(d["delta"], d["act"])
+        Wr, Mr = orc.sync_fc_sfb(U32, V32, d["W"], d["Mom"], lr, mu)
+        e = three_errors(d["W"], Wg, Mg, Wr, Mr)
+        assert max(e) <= tol_vs_unrounded, e
 
 
 @pytest.mark.parametrize("cfg", [3, 4])
-def test_sfb_bf16_full_size_sampled(cfg):
-    """Configs 3 and 4 at full size, in the launch shape the benchmark times; the oracle
-    evaluates 30 000 sampled outputs one by one (plus, for the softmax errors of config 4,
-    the zero column-sum property over whole columns)."""
+def test_sfb_bf16_full_size_whole_matrix(cfg):
+    """Configs 3 and 4 at full size, in the launch shape the benchmark times, compared with the
+    oracle over the WHOLE matrix: against the oracle fed the bf16-rounded factors (1e-5 and the
+    per-element bound) and against the oracle fed the unrounded fp32 factors (2e-2)."""
     d = inputs.fc_config(cfg)
-    N, M = d["N"], d["M"]
     Wg, Mg, _ = run_sfb(d, psd.BF16, inputs.LR, inputs.MU)
-    idx_n, idx_m = _sample_positions(N, M, 30000, seed=cfg)
-    W0s, M0s = d["W"][idx_n, idx_m], d["Mom"][idx_n, idx_m]
-    Ub, Vb = orc.pack_factors(d["delta"], d["act"], "bf16")
-    dWs = orc.rebuild_samples(Ub, Vb, idx_n, idx_m)
-    Wr, Mr = orc.momentum_update(dWs, W0s, M0s, inputs.LR, inputs.MU)
-    e = three_errors(W0s, Wg[idx_n, idx_m], Mg[idx_n, idx_m], Wr, Mr)
-    assert max(e) <= TOL_F32, e
-    U, V = orc.pack_factors(d["delta"], d["act"])
-    dWs = orc.rebuild_samples(U, V, idx_n, idx_m)
-    Wr, Mr = orc.momentum_update(dWs, W0s, M0s, inputs.LR, inputs.MU)
-    e = three_errors(W0s, Wg[idx_n, idx_m], Mg[idx_n, idx_m], Wr, Mr)
-    assert max(e) <= TOL_BF16_VS_F32, e
-    # every element was touched exactly once: Mom started at zero, W' = W - Mom' holds in fp32
-    assert np.array_equal(Wg, d["W"] - Mg)
+    _whole_matrix_checks(d, Wg, Mg, "bf16", inputs.LR, inputs.MU, tol_vs_unrounded=TOL_BF16_VS_F32)
     if cfg == 4:
         # rows of (softmax - onehot) sum to zero, so each column of dW sums to ~0
         col = Mg.astype(np.float64).sum(axis=0)
         assert np.abs(col).max() <= 2e-2 * np.abs(Mg.astype(np.float64)).sum(axis=0).max()
 
 
-@pytest.mark.parametrize("M,N,B,P,dtype", [
+@pytest.mark.parametrize("M,N,dtype", [(9216, 4096, psd.BF16), (4096, 21841, psd.BF16), (4096, 1000, psd.F32),
+                                       (9216, 4096, psd.F32)])
+def test_sfb_full_size_integer_factors_bit_exact(M, N, dtype):
+    """The production tile choice, the multi-round XCD raster, every ragged tile of N = 21841 and the
+    LDS ring in steady state (K = 2048), compared bit for bit: integer-valued factors keep every partial
+    sum below 2^24 (|u v| <= 9, K = 2048), so the fp32 result does not depend on the summation order."""
+    d = inputs.fc_layer_integer(M, N, 256, 8, seed=M + N + 7)
+    Wg, Mg, _ = run_sfb(d, dtype, 0.25, 0.5)
+    U, V = orc.pack_factors(d["delta"], d["act"])
+    Wr, Mr = orc.sync_fc_sfb(U, V, d["W"], d["Mom"], 0.25, 0.5)
+    assert np.array_equal(Mg, Mr), np.argwhere(Mg != Mr)[:8]
+    assert np.array_equal(Wg, Wr)
+
+
+SECOND_WORKLOAD = [
     (3000, 3000, 256, 8, psd.BF16),      # FC stack of the ImageNet-22K network (Section 5.1.3)
     (3000, 3000, 256, 8, psd.F32),
     (3000, 21841, 256, 8, psd.BF16),     # its 21 841-way classifier
     (1024, 1000, 32, 8, psd.BF16),       # GoogLeNet's single FC layer at batch 32 per node (Section 5.1.2)
     (1024, 1000, 32, 8, psd.F32),
-])
-def test_sfb_second_workload_shapes_sampled(M, N, B, P, dtype):
+    (25088, 4096, 8, 8, psd.BF16),       # VGG-16-sized FC stack (Table 3) at its batch of 64 (Table 2) over 8 workers
+    (25088, 4096, 8, 8, psd.F32),
+    (4096, 4096, 8, 8, psd.BF16),
+    (4096, 1000, 8, 8, psd.F32),
+]
+
+
+@pytest.mark.parametrize("M,N,B,P,dtype", SECOND_WORKLOAD)
+def test_sfb_second_workload_shapes_whole_matrix(M, N, B, P, dtype):
     d = inputs.fc_layer(M, N, B, P, seed=M + N + B, delta_kind="softmax" if N == 21841 else "gauss")
     Wg, Mg, _ = run_sfb(d, dtype, inputs.LR, inputs.MU)
-    idx_n, idx_m = _sample_positions(N, M, 20000, seed=N)
-    name = "f32" if dtype == psd.F32 else "bf16"
-    U, V = orc.pack_factors(d["delta"], d["act"], name)
-    dWs = orc.rebuild_samples(U, V, idx_n, idx_m)
-    W0s, M0s = d["W"][idx_n, idx_m], d["Mom"][idx_n, idx_m]
-    Wr, Mr = orc.momentum_update(dWs, W0s, M0s, inputs.LR, inputs.MU)
-    e = three_errors(W0s, Wg[idx_n, idx_m], Mg[idx_n, idx_m], Wr, Mr)
-    assert max(e) <= TOL_F32, e
-    assert np.array_equal(Wg, d["W"] - Mg)                # every weight updated exactly once
+    _whole_matrix_checks(d, Wg, Mg, "f32" if dtype == psd.F32 else "bf16", inputs.LR, inputs.MU)
+
+
+def test_sfb_vgg16_first_fc_layer_at_full_batch_integer_bit_exact():
+    # the widest factor matrix of any workload here (25088 inputs, K = 2048: 103 MB of bf16 activations)
+    d = inputs.fc_layer_integer(25088, 4096, 256, 8, seed=16)
+    Wg, Mg, _ = run_sfb(d, psd.BF16, 0.25, 0.5)
+    U, V = orc.pack_factors(d["delta"], d["act"])
+    Wr, Mr = orc.sync_fc_sfb(U, V, d["W"], d["Mom"], 0.25, 0.5)
+    assert np.array_equal(Mg, Mr) and np.array_equal(Wg, Wr)
 
 
 @pytest.mark.parametrize("M,N,B,P", [(16, 1, 1, 1), (40, 127, 3, 5), (64, 1000, 16, 8), (8, 21841, 4, 2), (32, 300, 1, 37)])
@@ -490,7 +514,7 @@ def test_iteration_scaled_down_matches_oracle_and_ignores_issue_order(factor_dty
 
 def test_iteration_full_size_in_the_benchmark_configuration():
     """Config 5 at full size, issued exactly as bench.py does (one stream per layer, Algorithm 3
-    routes, bf16 factors): conv layers compared whole, FC layers on 20 000 sampled weights each."""
+    routes, bf16 factors): every layer, conv and FC, compared whole with the oracle."""
     layers = inputs.cnn_iteration()
     streams = [torch.cuda.Stream(device=DEV) for _ in layers]
     tasks, state = _build_iteration(layers, psd.BF16, streams)
@@ -502,15 +526,9 @@ def test_iteration_full_size_in_the_benchmark_configuration():
         if L["kind"] == "conv":
             Wr, Mr = orc.sync_dense_ps(L["G"], L["W"], L["Mom"], inputs.LR, inputs.MU, inputs.CNN_S)
             e = three_errors(L["W"], Wg, Mg, Wr, Mr)
+            assert max(e) <= TOL_F32, (L["name"], e)
         else:
-            idx_n, idx_m = _sample_positions(L["N"], L["M"], 20000, seed=L["N"])
-            Ub, Vb = orc.pack_factors(L["delta"], L["act"], "bf16")
-            dWs = orc.rebuild_samples(Ub, Vb, idx_n, idx_m)
-            W0s, M0s = L["W"][idx_n, idx_m], L["Mom"][idx_n, idx_m]
-            Wr, Mr = orc.momentum_update(dWs, W0s, M0s, inputs.LR, inputs.MU)
-            e = three_errors(W0s, Wg[idx_n, idx_m], Mg[idx_n, idx_m], Wr, Mr)
-            assert np.array_equal(Wg, L["W"] - Mg)      # every weight updated exactly once
-        assert max(e) <= TOL_F32, (L["name"], e)
+            _whole_matrix_checks(L, Wg, Mg, "bf16", inputs.LR, inputs.MU)
 
 
 def test_iteration_waits_for_the_layers_gradient_event():

@@ -240,3 +240,14 @@ def test_dense_route_applies_the_same_weight_decay():
     W2, Mom2 = orc.sync_dense_ps(d["G"], d["W"], d["Mom"], lr=0.25, mu=0.5, S=4, wd=0.5)
     want_m = 0.5 * d["Mom"] + 0.25 * (g + 0.5 * d["W"])
     assert np.array_equal(Mom2, want_m) and np.array_equal(W2, d["W"] - want_m)
+
+
+def test_rel_frob_against_hand_values():
+    # |x - ref|_F / |ref|_F written out: 3-4-5 triangle, a constant matrix, and the zero reference
+    assert orc.rel_frob(np.array([3.3, 4.4]), np.array([3.0, 4.0])) == pytest.approx(0.1, rel=1e-12)
+    assert orc.rel_frob(np.full((2, 2), 2.0), np.ones((2, 2))) == pytest.approx(1.0, rel=1e-12)
+    assert orc.rel_frob(np.array([[1.0, 2.0], [3.0, 4.0]]), np.array([[1.0, 2.0], [3.0, 4.0]])) == 0.0
+    assert orc.rel_frob(np.array([0.0, 2.0]), np.zeros(2)) == pytest.approx(2.0)     # zero reference: absolute norm
+    # float32 inputs are widened before the subtraction (no fp32 cancellation error)
+    a = np.array([1.0 + 2.0 ** -23], dtype=np.float32)
+    assert orc.rel_frob(a, np.array([1.0])) == pytest.approx(2.0 ** -23, rel=1e-12)
