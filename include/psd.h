@@ -36,7 +36,8 @@ enum {
     PSD_E_NULL = -2,        /* a required pointer is NULL */
     PSD_E_UNSUPPORTED = -3, /* valid request this build cannot serve (e.g. route needs data not given) */
     PSD_E_OVERFLOW = -4,    /* a communication volume does not fit in 64 bits */
-    PSD_E_HIP = -5          /* a HIP call failed; see psd_last_hip_error() */
+    PSD_E_HIP = -5,         /* a HIP call failed; see psd_last_hip_error() */
+    PSD_E_WORKSPACE = -6    /* a workspace was passed that is smaller than psd_sfb_workspace_bytes() asks for */
 };
 
 enum { PSD_LAYER_CONV = 0, PSD_LAYER_FC = 1 };                      /* layer kind       */
@@ -102,10 +103,25 @@ psd_status psd_pack_factors(const psd_plan* plan, const float* const* delta_p,
  * W, Mom [dev] N x M fp32 row-major, updated in place; dW is never stored.
  * fp32 factors: fp32 MFMA, fp32 accumulation.  bf16 factors: bf16 MFMA with fp32
  * accumulation; W and Mom stay fp32.  The same call serves the SF_PS route (the server
- * runs the identical reconstruction over the same P*B factors). */
+ * runs the identical reconstruction over the same P*B factors).
+ *
+ * workspace [dev] (optional): scratch for layers with so few output tiles (128 x 128 weights each)
+ * that most compute units would get none (e.g. a 1024 -> 1000 classifier).  With workspace_bytes == 0 (workspace may be NULL) every tile is contracted
+ * over all of K by one workgroup.  With a workspace of at least psd_sfb_workspace_bytes() bytes,
+ * 16-byte aligned, the sum over k is split over up to 4 workgroups per tile: each stores a partial dW
+ * (N x M fp32) to the workspace, then the partials are added in split order and the update is applied
+ * (same arithmetic; only the order of the fp32 additions over k changes).  A non-zero workspace_bytes
+ * below the queried size is refused with PSD_E_WORKSPACE.  The workspace is not retained; its contents
+ * after the call are unspecified; calls that share one workspace must not overlap in time. */
 psd_status psd_sync_fc_sfb(const psd_plan* plan, int32_t factor_dtype,
                            const void* U, int64_t ldu, const void* V, int64_t ldv,
-                           float* W, float* Mom, float lr, float mu, float wd, void* stream);
+                           float* W, float* Mom, float lr, float mu, float wd,
+                           void* workspace, size_t workspace_bytes, void* stream);
+
+/* Bytes of workspace with which psd_sync_fc_sfb would split this layer's sum over k (a multiple of
+ * 16), or 0 if it would not split it (enough tiles already, K too short, bad arguments).  Host only;
+ * depends on the layer shape, the factor dtype, the current device's CU count and the pinned tile. */
+size_t psd_sfb_workspace_bytes(const psd_plan* plan, int32_t factor_dtype);
 
 /* Bias of an FC layer under SFB.  For z = W a + b the per-sample gradient w.r.t. b is the error
  * vector itself (the chain rule behind Eq. 5), so with the stacked errors U of the layer
@@ -154,6 +170,8 @@ typedef struct psd_layer_task {
     const float* const* G;     /* PS route: [host] P [dev] pointers, M*N fp32 each (may be
                                   NULL for an FC layer that is routed to SFB / SF_PS) */
     float* W; float* Mom;      /* [dev] N x M fp32 */
+    void* workspace;           /* FC: optional [dev] scratch of workspace_bytes bytes (see psd_sync_fc_sfb) */
+    size_t workspace_bytes;    /* 0 = none */
     void* stream;              /* the stream this layer's work is enqueued on */
     void* ev_ready;            /* optional hipEvent_t (or NULL): the layer's stream waits for it before any
                                   of the layer's work starts -- "the gradient of this layer exists"

@@ -14,7 +14,7 @@ import torch
 _PKG = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_PKG, "libpsd.so")
 
-OK, E_INVALID, E_NULL, E_UNSUPPORTED, E_OVERFLOW, E_HIP = 0, -1, -2, -3, -4, -5
+OK, E_INVALID, E_NULL, E_UNSUPPORTED, E_OVERFLOW, E_HIP, E_WORKSPACE = 0, -1, -2, -3, -4, -5, -6
 LAYER_CONV, LAYER_FC = 0, 1
 ROUTE_PS_DENSE, ROUTE_SFB, ROUTE_SF_PS = 0, 1, 2
 RULE_ALG3, RULE_SFB_VS_DENSE = 0, 1
@@ -50,7 +50,8 @@ class LayerTask(ctypes.Structure):
     _fields_ = [("plan", Plan), ("factor_dtype", ctypes.c_int32), ("S", ctypes.c_int32),
                 ("delta_p", _f32pp), ("act_p", _f32pp),
                 ("U", ctypes.c_void_p), ("ldu", ctypes.c_int64), ("V", ctypes.c_void_p), ("ldv", ctypes.c_int64),
-                ("G", _f32pp), ("W", _f32p), ("Mom", _f32p), ("stream", ctypes.c_void_p),
+                ("G", _f32pp), ("W", _f32p), ("Mom", _f32p), ("workspace", ctypes.c_void_p),
+                ("workspace_bytes", ctypes.c_size_t), ("stream", ctypes.c_void_p),
                 ("ev_ready", ctypes.c_void_p), ("ev_begin", ctypes.c_void_p), ("ev_end", ctypes.c_void_p)]
 
 
@@ -74,7 +75,9 @@ SIGNATURES = {
                                           ctypes.c_int64, ctypes.c_void_p, ctypes.c_int64, ctypes.c_void_p]),
     "psd_sync_fc_sfb": (ctypes.c_int32, [ctypes.POINTER(Plan), ctypes.c_int32, ctypes.c_void_p, ctypes.c_int64,
                                          ctypes.c_void_p, ctypes.c_int64, ctypes.c_void_p, ctypes.c_void_p,
-                                         ctypes.c_float, ctypes.c_float, ctypes.c_float, ctypes.c_void_p]),
+                                         ctypes.c_float, ctypes.c_float, ctypes.c_float, ctypes.c_void_p,
+                                         ctypes.c_size_t, ctypes.c_void_p]),
+    "psd_sfb_workspace_bytes": (ctypes.c_size_t, [ctypes.POINTER(Plan), ctypes.c_int32]),
     "psd_sync_fc_bias": (ctypes.c_int32, [ctypes.POINTER(Plan), ctypes.c_int32, ctypes.c_void_p, ctypes.c_int64,
                                           ctypes.c_void_p, ctypes.c_void_p, ctypes.c_float, ctypes.c_float,
                                           ctypes.c_float, ctypes.c_void_p]),
@@ -188,13 +191,32 @@ def pack_factors(plan, delta, act, out_dtype, U, ldu, V, ldv, stream=None):
            "psd_pack_factors")
 
 
-def sync_fc_sfb(plan, factor_dtype, U, ldu, V, ldv, W, Mom, lr, mu, stream=None, wd=0.0):
+def sfb_workspace_bytes(plan, factor_dtype):
+    return int(lib().psd_sfb_workspace_bytes(ctypes.byref(plan), factor_dtype))
+
+
+def alloc_workspace(plan, factor_dtype, device="cuda"):
+    """Device scratch of the queried size, or None if the layer would not use one.  Memory only."""
+    n = sfb_workspace_bytes(plan, factor_dtype)
+    return torch.empty(n // 4, dtype=torch.float32, device=device) if n else None
+
+
+def _workspace_args(workspace):
+    if workspace is None:
+        return None, 0
+    if not (isinstance(workspace, torch.Tensor) and workspace.is_cuda and workspace.is_contiguous()):
+        raise ValueError("workspace must be a contiguous CUDA tensor")
+    return workspace.data_ptr(), workspace.numel() * workspace.element_size()
+
+
+def sync_fc_sfb(plan, factor_dtype, U, ldu, V, ldv, W, Mom, lr, mu, stream=None, wd=0.0, workspace=None):
     up = _dev_ptr(U, _FACTOR_TORCH.get(factor_dtype, ()), plan.K * ldu, "U")
     vp = _dev_ptr(V, _FACTOR_TORCH.get(factor_dtype, ()), plan.K * ldv, "V")
     wp = _dev_ptr(W, torch.float32, plan.N * plan.M, "W")
     mp = _dev_ptr(Mom, torch.float32, plan.N * plan.M, "Mom")
+    ws, ws_bytes = _workspace_args(workspace)
     _check(lib().psd_sync_fc_sfb(ctypes.byref(plan), factor_dtype, up, ldu, vp, ldv, wp, mp, lr, mu, wd,
-                                 _stream_handle(stream)), "psd_sync_fc_sfb")
+                                 ws, ws_bytes, _stream_handle(stream)), "psd_sync_fc_sfb")
 
 
 def sync_fc_bias(plan, factor_dtype, U, ldu, bias, mom_bias, lr, mu, stream=None, wd=0.0):
@@ -233,7 +255,7 @@ def sync_dense_ps_multi(layers, lr, mu, stream=None, wd=0.0):
 class Iteration:
     """Marshalled, reusable argument block for psd_sync_iteration (layers bottom-up).
 
-    Each layer is a dict: FC  -> plan, factor_dtype, delta, act, U, ldu, V, ldv, W, Mom, stream
+    Each layer is a dict: FC  -> plan, factor_dtype, delta, act, U, ldu, V, ldv, W, Mom, stream[, workspace]
                          conv -> plan, G, S, W, Mom, stream
     plus optional ev_ready (the layer's stream waits for it first) and ev_begin / ev_end (recorded
     around the layer's sync kernel); all raw hipEvent_t handles as ints.
@@ -251,6 +273,8 @@ class Iteration:
             t.W = ctypes.cast(_dev_ptr(L["W"], torch.float32, n, "W"), _f32p)
             t.Mom = ctypes.cast(_dev_ptr(L["Mom"], torch.float32, n, "Mom"), _f32p)
             t.stream = _stream_handle(L.get("stream"))
+            t.workspace, t.workspace_bytes = _workspace_args(L.get("workspace"))
+            self._keep.append(L.get("workspace"))
             t.ev_ready = L.get("ev_ready")
             t.ev_begin, t.ev_end = L.get("ev_begin"), L.get("ev_end")   # raw hipEvent_t handles or None
             t.S = L.get("S", 1)

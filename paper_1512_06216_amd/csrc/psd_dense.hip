@@ -165,4 +165,17 @@ psd_status launch_dense_wide(const DenseWide& a, float lr, float mu, float wd, h
     return PSD_OK;
 }
 
+// Second stage of a split reconstruction: the `splits` partial dW matrices are exactly "several dense
+// copies of one gradient", so the parameter-server kernel sums them (in split order) and updates.
+psd_status launch_sfb_reduce(const float* part, int splits, int64_t N, int64_t M, float* W, float* Mom, float lr,
+                             float mu, float wd, hipStream_t st)
+{
+    DenseWide a;
+    for (int p = 0; p < PSD_MAX_WORKERS; ++p) a.G[p] = p < splits ? part + p * sfb_part_stride(N, M) : nullptr;
+    a.W = W; a.Mom = Mom; a.n = N * M; a.P = splits; a.S = 1;
+    a.q = a.n; a.r = 0;
+    a.chunks = dense_chunks_for(a.n, 1);
+    return launch_dense_wide(a, lr, mu, wd, st);
+}
+
 }  // namespace psd

@@ -78,6 +78,7 @@ const char* psd_status_string(psd_status s)
         case PSD_E_UNSUPPORTED: return "unsupported request";
         case PSD_E_OVERFLOW: return "communication volume overflows 64 bits";
         case PSD_E_HIP: return "HIP call failed (see psd_last_hip_error)";
+        case PSD_E_WORKSPACE: return "workspace smaller than psd_sfb_workspace_bytes asks for";
         default: return "unknown status";
     }
 }
@@ -154,8 +155,18 @@ psd_status psd_pack_factors(const psd_plan* plan, const float* const* delta_p, c
     return launch_pack(a, out_dtype, st);
 }
 
+size_t psd_sfb_workspace_bytes(const psd_plan* plan, int32_t factor_dtype)
+{
+    if (!plan || !valid_plan_sizes(plan) || (factor_dtype != PSD_F32 && factor_dtype != PSD_BF16)) return 0;
+    const int64_t K = plan->P * plan->B;
+    const int splits = factor_dtype == PSD_F32 ? sfb_f32_splits(plan->N, plan->M, K) : sfb_bf16_splits(plan->N, plan->M, K);
+    if (splits <= 1) return 0;
+    return static_cast<size_t>(splits) * static_cast<size_t>(sfb_part_stride(plan->N, plan->M)) * sizeof(float);
+}
+
 psd_status psd_sync_fc_sfb(const psd_plan* plan, int32_t factor_dtype, const void* U, int64_t ldu,
-                           const void* V, int64_t ldv, float* W, float* Mom, float lr, float mu, float wd, void* stream)
+                           const void* V, int64_t ldv, float* W, float* Mom, float lr, float mu, float wd,
+                           void* workspace, size_t workspace_bytes, void* stream)
 {
     if (!plan || !U || !V || !W || !Mom) return PSD_E_NULL;
     if (factor_dtype != PSD_F32 && factor_dtype != PSD_BF16) return PSD_E_INVALID;
@@ -164,13 +175,23 @@ psd_status psd_sync_fc_sfb(const psd_plan* plan, int32_t factor_dtype, const voi
     if (!valid_ld(ldu, plan->N, factor_dtype) || !valid_ld(ldv, plan->M, factor_dtype)) return PSD_E_INVALID;
     if (!aligned16(U) || !aligned16(V) || !aligned16(W) || !aligned16(Mom)) return PSD_E_INVALID;
     if (W == Mom) return PSD_E_INVALID;
+    // no workspace: one workgroup per tile over all of K.  A workspace: the split the query sized it for.
+    int splits = 1;
+    if (workspace_bytes != 0) {
+        if (!workspace) return PSD_E_NULL;
+        if (!aligned16(workspace)) return PSD_E_INVALID;
+        const size_t need = psd_sfb_workspace_bytes(plan, factor_dtype);
+        if (workspace_bytes < need) return PSD_E_WORKSPACE;
+        if (need != 0) splits = static_cast<int>(need / (static_cast<size_t>(sfb_part_stride(plan->N, plan->M)) * sizeof(float)));
+    }
     hipStream_t st = static_cast<hipStream_t>(stream);
     const int64_t K = plan->P * plan->B;
+    float* part = splits > 1 ? static_cast<float*>(workspace) : nullptr;
     if (factor_dtype == PSD_F32)
         return launch_sfb_f32(static_cast<const float*>(U), ldu, static_cast<const float*>(V), ldv, W, Mom,
-                              plan->N, plan->M, K, lr, mu, wd, st);
+                              plan->N, plan->M, K, lr, mu, wd, part, splits, st);
     return launch_sfb_bf16(static_cast<const uint16_t*>(U), ldu, static_cast<const uint16_t*>(V), ldv, W, Mom,
-                           plan->N, plan->M, K, lr, mu, wd, st);
+                           plan->N, plan->M, K, lr, mu, wd, part, splits, st);
 }
 
 psd_status psd_sync_fc_bias(const psd_plan* plan, int32_t factor_dtype, const void* U, int64_t ldu, float* bias,
@@ -267,7 +288,8 @@ psd_status psd_sync_iteration(int32_t L, const psd_layer_task* layers, float lr,
             r = psd_pack_factors(&t.plan, t.delta_p, t.act_p, t.factor_dtype, t.U, t.ldu, t.V, t.ldv, t.stream);
             if (r == PSD_OK && t.ev_begin) PSD_HIP_TRY(hipEventRecord(static_cast<hipEvent_t>(t.ev_begin), st));
             if (r == PSD_OK)
-                r = psd_sync_fc_sfb(&t.plan, t.factor_dtype, t.U, t.ldu, t.V, t.ldv, t.W, t.Mom, lr, mu, wd, t.stream);
+                r = psd_sync_fc_sfb(&t.plan, t.factor_dtype, t.U, t.ldu, t.V, t.ldv, t.W, t.Mom, lr, mu, wd, t.workspace,
+                                    t.workspace_bytes, t.stream);
         } else {
             return PSD_E_INVALID;
         }

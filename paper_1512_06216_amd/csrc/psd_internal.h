@@ -60,10 +60,37 @@ struct PackArgs {
 };
 psd_status launch_pack(const PackArgs& a, int32_t out_dtype, hipStream_t st);
 
+// ---- reconstruction.  part / splits: with splits > 1 the contraction is split over `splits`
+// workgroups per tile, each storing a partial dW (N x M, sfb_part_stride apart) to `part`, and the
+// partials are summed in split order and the update applied by launch_sfb_reduce.
 psd_status launch_sfb_f32(const float* U, int64_t ldu, const float* V, int64_t ldv, float* W, float* Mom,
-                          int64_t N, int64_t M, int64_t K, float lr, float mu, float wd, hipStream_t st);
+                          int64_t N, int64_t M, int64_t K, float lr, float mu, float wd, float* part, int splits,
+                          hipStream_t st);
 psd_status launch_sfb_bf16(const uint16_t* U, int64_t ldu, const uint16_t* V, int64_t ldv, float* W, float* Mom,
-                           int64_t N, int64_t M, int64_t K, float lr, float mu, float wd, hipStream_t st);
+                           int64_t N, int64_t M, int64_t K, float lr, float mu, float wd, float* part, int splits,
+                           hipStream_t st);
+// how many ways each kernel would split K for this layer when it is given a workspace (1 = not at all)
+int sfb_f32_splits(int64_t N, int64_t M, int64_t K);
+int sfb_bf16_splits(int64_t N, int64_t M, int64_t K);
+psd_status launch_sfb_reduce(const float* part, int splits, int64_t N, int64_t M, float* W, float* Mom, float lr,
+                             float mu, float wd, hipStream_t st);
+
+constexpr int kMaxSplits = 4;
+// Split only for layers that leave most of the chip idle: while the split workgroups still number at
+// most one per CU (half the slots) and every split keeps at least kMinSplitRows k rows.  A split
+// costs 8 extra bytes of HBM traffic per weight and split (partial written, then read) plus a second
+// launch.  Measured: 64 tiles (1024 -> 1000, K = 8192) 64 -> 32 us, 16 tiles (512 -> 512, K = 16384)
+// 115 -> 37 us; but 256 tiles (4096 -> 1000, one workgroup per CU already) lose at every K tried
+// (K = 2048: 39 -> 49 us, K = 8192: 103 -> 107 us), so such layers are not split.
+constexpr int64_t kMinSplitRows = 512;
+inline int sfb_splits_for(int64_t tiles, int64_t slots, int64_t K)
+{
+    int s = 1;
+    while (s < kMaxSplits && tiles * (s + 1) <= slots / 2 && K / (s + 1) >= kMinSplitRows) ++s;
+    return s;
+}
+// elements between two partials: N*M rounded up so that every partial starts 16-byte aligned
+inline int64_t sfb_part_stride(int64_t N, int64_t M) { return (N * M + 3) / 4 * 4; }
 
 psd_status launch_bias(const void* U, int64_t ldu, int32_t dtype, int64_t N, int64_t K, float* bias, float* mom,
                        float lr, float mu, float wd, hipStream_t st);

@@ -59,11 +59,17 @@ __device__ __forceinline__ bf16x4 read_tr(uint32_t lds_addr)
     return __builtin_amdgcn_ds_read_tr16_b64_v4bf16(reinterpret_cast<lds_bf16x4*>(lds_addr));
 }
 
-template <class C>
+// PART = false: one workgroup per tile contracts over all of K and applies the update.
+// PART = true (layers with too few tiles to fill the chip): the grid holds `splits` workgroups per
+// tile, workgroup (tile, s) contracts over k-stages [s * stages_per_split, (s+1) * stages_per_split)
+// and stores its partial dW tile to part + s * part_stride (N x M row-major); the partials are summed
+// in split order and the update applied by the parameter-server sum kernel afterwards.
+template <class C, bool PART>
 __global__ void __launch_bounds__(C::THREADS, C::OCC)
 sfb_bf16_kernel(const uint16_t* __restrict__ U, int64_t ldu, const uint16_t* __restrict__ V, int64_t ldv,
                 float* __restrict__ W, float* __restrict__ Mom, int N, int M, int K, float lr, float mu, float wd,
-                int tiles_n, int tiles_m, uint32_t u_bytes, uint32_t v_bytes)
+                int tiles_n, int tiles_m, uint32_t u_bytes, uint32_t v_bytes, float* __restrict__ part,
+                int64_t part_stride, int stages_per_split)
 {
     extern __shared__ __attribute__((aligned(1024))) uint16_t lds[];
     const uint32_t lds0 = static_cast<uint32_t>(reinterpret_cast<uintptr_t>(
@@ -73,7 +79,8 @@ sfb_bf16_kernel(const uint16_t* __restrict__ U, int64_t ldu, const uint16_t* __r
     // XCD a contiguous run of the tile sequence, and order that sequence in groups of GROUP_N
     // tile rows so that the workgroups sharing an L2 re-use the same few U and V panels.
     const int T = tiles_n * tiles_m;
-    const int b = blockIdx.x, xcd = b & 7;
+    const int split = PART ? __builtin_amdgcn_readfirstlane(blockIdx.x / T) : 0;   // (the division runs on the vector ALU)
+    const int b = PART ? blockIdx.x - split * T : blockIdx.x, xcd = b & 7;
     const int lin = xcd * (T >> 3) + (xcd < (T & 7) ? xcd : (T & 7)) + (b >> 3);
     const int per_group = GROUP_N * tiles_m;
     const int g = lin / per_group, in_g = lin - g * per_group;
@@ -90,6 +97,14 @@ sfb_bf16_kernel(const uint16_t* __restrict__ U, int64_t ldu, const uint16_t* __r
     // of rows, or row fragments for 384-byte rows), lane i carrying the chunk that belongs at
     // physical position i of that run.
     // physical chunk pc of row r holds logical chunk pc ^ ((r & 3) << 1)
+    // this workgroup's k range: rows at or past k_end read as zeros (descriptor size), rows before
+    // k_begin are skipped (offsets)
+    const int k_begin = PART ? split * stages_per_split * KT : 0;
+    const int k_end = PART ? (k_begin + stages_per_split * KT < K ? k_begin + stages_per_split * KT : K) : K;
+    if constexpr (PART) {
+        u_bytes = __builtin_amdgcn_readfirstlane(static_cast<uint32_t>(int64_t(k_end) * ldu * 2));
+        v_bytes = __builtin_amdgcn_readfirstlane(static_cast<uint32_t>(int64_t(k_end) * ldv * 2));
+    }
     const i32x4 rsrc_u = raw_rsrc(U, u_bytes), rsrc_v = raw_rsrc(V, v_bytes);
     uint32_t voff_a[C::NI_A], voff_b[C::NI_B];
     {
@@ -99,7 +114,7 @@ sfb_bf16_kernel(const uint16_t* __restrict__ U, int64_t ldu, const uint16_t* __r
             const int f = (wave * C::NI_A + j) * 64 + lane;   // chunk index inside the stage
             const int r = f / LPR;
             const int lc = (f % LPR) ^ ((r & 3) << 1);
-            voff_a[j] = static_cast<uint32_t>((r * ldu + n0 + lc * 8) * 2);
+            voff_a[j] = static_cast<uint32_t>(((k_begin + r) * ldu + n0 + lc * 8) * 2);
         }
     }
     {
@@ -109,7 +124,7 @@ sfb_bf16_kernel(const uint16_t* __restrict__ U, int64_t ldu, const uint16_t* __r
             const int f = (wave * C::NI_B + j) * 64 + lane;
             const int r = f / LPR;
             const int lc = (f % LPR) ^ ((r & 3) << 1);
-            voff_b[j] = static_cast<uint32_t>((r * ldv + m0 + lc * 8) * 2);
+            voff_b[j] = static_cast<uint32_t>(((k_begin + r) * ldv + m0 + lc * 8) * 2);
         }
     }
     const uint32_t step_a = static_cast<uint32_t>(KT * ldu * 2), step_b = static_cast<uint32_t>(KT * ldv * 2);
@@ -176,7 +191,7 @@ sfb_bf16_kernel(const uint16_t* __restrict__ U, int64_t ldu, const uint16_t* __r
                 acc[bn][bm] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bb[bm], a[bn], acc[bn][bm], 0, 0, 0);
     };
 
-    const int steps = (K + KT - 1) / KT;
+    const int steps = k_end > k_begin ? (k_end - k_begin + KT - 1) / KT : 0;
     constexpr int LPS = C::NI_A + C::NI_B;       // DMA instructions per wavefront per stage
     auto stage_base = [&](int t) { return lds0 + static_cast<uint32_t>(t % C::NSTAGE) * C::STAGE_BYTES; };
 
@@ -236,6 +251,16 @@ sfb_bf16_kernel(const uint16_t* __restrict__ U, int64_t ldu, const uint16_t* __r
                                     acc[bn][bm][4 * q + 3]);
                 float4 d[4], w[4], mo[4];
                 const int64_t m = m0 + wm0 + 32 * bm + pcol;
+                if constexpr (PART) {
+                    float* dst = part + split * part_stride;
+#pragma unroll
+                    for (int jj = 0; jj < 4; ++jj) {
+                        const int64_t n = n0 + wn0 + 32 * bn + prow + 8 * jj;
+                        d[jj] = *reinterpret_cast<const float4*>(patch + (prow + 8 * jj) * PLD + pcol);
+                        if (n < N && m < M) *reinterpret_cast<float4*>(dst + n * int64_t(M) + m) = d[jj];
+                    }
+                    continue;
+                }
 #pragma unroll
                 for (int jj = 0; jj < 4; ++jj) {
                     const int64_t n = n0 + wn0 + 32 * bn + prow + 8 * jj;
@@ -272,6 +297,10 @@ sfb_bf16_kernel(const uint16_t* __restrict__ U, int64_t ldu, const uint16_t* __r
 #pragma unroll
                 for (int r = 0; r < 16; ++r) {
                     const int64_t m = m0 + wm0 + 32 * bm + 8 * (r >> 2) + 4 * lhi + (r & 3);
+                    if constexpr (PART) {
+                        if (m < M) part[split * part_stride + n * int64_t(M) + m] = acc[bn][bm][r];
+                        continue;
+                    }
                     if (m < M) {
                         float wv = wrow[m], mv = mrow[m];
                         upd(acc[bn][bm][r], wv, mv, lr, mu, wd);
@@ -285,29 +314,35 @@ sfb_bf16_kernel(const uint16_t* __restrict__ U, int64_t ldu, const uint16_t* __r
 
 template <class C>
 psd_status launch_cfg(const uint16_t* U, int64_t ldu, const uint16_t* V, int64_t ldv, float* W, float* Mom,
-                      int64_t N, int64_t M, int64_t K, float lr, float mu, float wd, hipStream_t st)
+                      int64_t N, int64_t M, int64_t K, float lr, float mu, float wd, float* part, int splits,
+                      hipStream_t st)
 {
     const int64_t tiles_n = (N + C::TN - 1) / C::TN, tiles_m = (M + C::TM - 1) / C::TM;
     const int64_t tiles = tiles_n * tiles_m;
-    if (tiles < 1 || tiles > 0x3fffffff) return PSD_E_INVALID;
+    if (tiles < 1 || tiles * splits > 0x3fffffff) return PSD_E_INVALID;
     // 32-bit byte offsets into each factor matrix, with room for the stages of read-ahead
     const int64_t u_bytes = K * ldu * 2, v_bytes = K * ldv * 2;
     const int64_t reach = (int64_t(1) << 32) - (C::NSTAGE + 2) * KT * (ldu > ldv ? ldu : ldv) * 2 - 4096;
     if (u_bytes > reach || v_bytes > reach) return PSD_E_UNSUPPORTED;
-    auto kern = sfb_bf16_kernel<C>;
+    auto kern = splits > 1 ? sfb_bf16_kernel<C, true> : sfb_bf16_kernel<C, false>;
     // raise the dynamic LDS limit once per process (idempotent, so a race between two first
     // callers is harmless; the flag only saves the call on later launches)
     static std::atomic<bool> attr_done{false};
     if (!attr_done.load(std::memory_order_acquire)) {
-        PSD_HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
+        PSD_HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(sfb_bf16_kernel<C, true>),
+                                        hipFuncAttributeMaxDynamicSharedMemorySize, int(C::LDS_BYTES)));
+        PSD_HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(sfb_bf16_kernel<C, false>),
                                         hipFuncAttributeMaxDynamicSharedMemorySize, int(C::LDS_BYTES)));
         attr_done.store(true, std::memory_order_release);
     }
-    hipLaunchKernelGGL(kern, dim3(static_cast<uint32_t>(tiles)), dim3(C::THREADS), C::LDS_BYTES, st, U, ldu, V, ldv, W,
-                       Mom, static_cast<int>(N), static_cast<int>(M), static_cast<int>(K), lr, mu, wd,
+    const int64_t stages = (K + KT - 1) / KT;
+    const int sps = static_cast<int>((stages + splits - 1) / splits);
+    hipLaunchKernelGGL(kern, dim3(static_cast<uint32_t>(tiles * splits)), dim3(C::THREADS), C::LDS_BYTES, st, U, ldu, V,
+                       ldv, W, Mom, static_cast<int>(N), static_cast<int>(M), static_cast<int>(K), lr, mu, wd,
                        static_cast<int>(tiles_n), static_cast<int>(tiles_m), static_cast<uint32_t>(u_bytes),
-                       static_cast<uint32_t>(v_bytes));
+                       static_cast<uint32_t>(v_bytes), part, sfb_part_stride(N, M), sps);
     PSD_HIP_TRY(hipGetLastError());
+    if (splits > 1) return launch_sfb_reduce(part, splits, N, M, W, Mom, lr, mu, wd, st);
     return PSD_OK;
 }
 
@@ -317,29 +352,51 @@ using Cfg128x128w4 = Cfg<2, 2, 2, 2, 4, 2>;   // small layers: more workgroups (
 
 }  // namespace
 
-psd_status launch_sfb_bf16(const uint16_t* U, int64_t ldu, const uint16_t* V, int64_t ldv, float* W, float* Mom,
-                           int64_t N, int64_t M, int64_t K, float lr, float mu, float wd, hipStream_t st)
+namespace {
+struct Bf16Tile { int id, tn, tm; };
+// tile choice (and, with a workspace, the split of K) for one layer
+void choose_bf16(int64_t N, int64_t M, int64_t K, bool may_split, Bf16Tile* tile, int* splits)
 {
+    static const Bf16Tile tiles_by_id[] = {{0, 128, 256}, {1, 128, 192}, {2, 128, 128}};
+    const int64_t slots = int64_t(device_cu_count()) * 2;
     int pick = tune_value(PSD_TUNE_SFB_BF16_TILE);
-    if (pick < 0) {
+    if (pick < 0 || pick > 2) {
         // Workgroups of one launch run in rounds of (CUs x workgroups per CU); a partly filled last
         // round costs as much as a full one.  Pick the tile whose rounds x tile area is smallest
         // (ties go to the larger tile; the 128 x 128 tile pays ~10% for its lower MFMA duty).
-        const int64_t slots = int64_t(device_cu_count()) * 2;
-        struct Cand { int id, tn, tm, weight; };
-        const Cand cands[] = {{0, 128, 256, 100}, {1, 128, 192, 100}, {2, 128, 128, 110}};
+        const int weight[] = {100, 100, 110};
         int64_t best = -1;
-        for (const Cand& c : cands) {
+        for (const Bf16Tile& c : tiles_by_id) {
             const int64_t tiles = ((N + c.tn - 1) / c.tn) * ((M + c.tm - 1) / c.tm);
-            const int64_t cost = ((tiles + slots - 1) / slots) * c.tn * c.tm * c.weight;
+            const int64_t cost = ((tiles + slots - 1) / slots) * c.tn * c.tm * weight[c.id];
             if (best < 0 || cost < best) { best = cost; pick = c.id; }
         }
     }
-    switch (pick) {
-        case 0: return launch_cfg<Cfg128x256w4>(U, ldu, V, ldv, W, Mom, N, M, K, lr, mu, wd, st);
-        case 1: return launch_cfg<Cfg128x192w4>(U, ldu, V, ldv, W, Mom, N, M, K, lr, mu, wd, st);
-        case 2: return launch_cfg<Cfg128x128w4>(U, ldu, V, ldv, W, Mom, N, M, K, lr, mu, wd, st);
-        default: return PSD_E_INVALID;
+    *tile = tiles_by_id[pick];
+    const int64_t tiles = ((N + tile->tn - 1) / tile->tn) * ((M + tile->tm - 1) / tile->tm);
+    *splits = may_split ? sfb_splits_for(tiles, slots, K) : 1;
+}
+}  // namespace
+
+int sfb_bf16_splits(int64_t N, int64_t M, int64_t K)
+{
+    Bf16Tile t;
+    int s;
+    choose_bf16(N, M, K, true, &t, &s);
+    return s;
+}
+
+psd_status launch_sfb_bf16(const uint16_t* U, int64_t ldu, const uint16_t* V, int64_t ldv, float* W, float* Mom,
+                           int64_t N, int64_t M, int64_t K, float lr, float mu, float wd, float* part, int splits,
+                           hipStream_t st)
+{
+    Bf16Tile t;
+    int unused;
+    choose_bf16(N, M, K, false, &t, &unused);
+    switch (t.id) {
+        case 0: return launch_cfg<Cfg128x256w4>(U, ldu, V, ldv, W, Mom, N, M, K, lr, mu, wd, part, splits, st);
+        case 1: return launch_cfg<Cfg128x192w4>(U, ldu, V, ldv, W, Mom, N, M, K, lr, mu, wd, part, splits, st);
+        default: return launch_cfg<Cfg128x128w4>(U, ldu, V, ldv, W, Mom, N, M, K, lr, mu, wd, part, splits, st);
     }
 }
 

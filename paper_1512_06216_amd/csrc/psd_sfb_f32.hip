@@ -34,11 +34,16 @@ constexpr int NSTAGE = 4;           // ring depth
 
 // BN = MFMA blocks per wavefront along n: workgroup tile (64*BN) x 128, wavefront tile (32*BN) x 64.
 // BN = 2 is the default; BN = 1 doubles the number of workgroups for layers with few tiles.
-template <int BN>
+// PART = true (layers with too few tiles to fill the chip): `splits` workgroups per tile, workgroup
+// (tile, s) contracts over k-stages [s * stages_per_split, (s+1) * stages_per_split) and stores its
+// partial dW tile to part + s * part_stride (N x M row-major); the partials are summed in split order
+// and the update applied by the parameter-server sum kernel afterwards.
+template <int BN, bool PART>
 __global__ void __launch_bounds__(THREADS)
 sfb_f32_kernel(const float* __restrict__ U, int64_t ldu, const float* __restrict__ V, int64_t ldv,
                float* __restrict__ W, float* __restrict__ Mom, int N, int M, int K, float lr, float mu, float wd,
-               int tiles_m, uint32_t u_bytes, uint32_t v_bytes)
+               int tiles_m, int tiles, uint32_t u_bytes, uint32_t v_bytes, float* __restrict__ part,
+               int64_t part_stride, int stages_per_split)
 {
     constexpr int TN = 64 * BN;
     constexpr int RA = TN * 4, RB = TM * 4;                       // LDS row bytes
@@ -49,7 +54,17 @@ sfb_f32_kernel(const float* __restrict__ U, int64_t ldu, const float* __restrict
     const uint32_t lds0 = static_cast<uint32_t>(reinterpret_cast<uintptr_t>(
         (__attribute__((address_space(3))) void*)lds));
 
-    const int tile_n = blockIdx.x / tiles_m, tile_m = blockIdx.x % tiles_m;
+    const int split = PART ? __builtin_amdgcn_readfirstlane(blockIdx.x / tiles) : 0;   // (the division runs on the vector ALU)
+    const int tile = PART ? blockIdx.x - split * tiles : blockIdx.x;
+    const int tile_n = tile / tiles_m, tile_m = tile % tiles_m;
+    // this workgroup's k range: rows at or past k_end read as zeros (descriptor size), rows before
+    // k_begin are skipped (offsets)
+    const int k_begin = PART ? split * stages_per_split * KT : 0;
+    const int k_end = PART ? (k_begin + stages_per_split * KT < K ? k_begin + stages_per_split * KT : K) : K;
+    if constexpr (PART) {
+        u_bytes = __builtin_amdgcn_readfirstlane(static_cast<uint32_t>(int64_t(k_end) * ldu * 4));
+        v_bytes = __builtin_amdgcn_readfirstlane(static_cast<uint32_t>(int64_t(k_end) * ldv * 4));
+    }
     const int64_t n0 = int64_t(tile_n) * TN, m0 = int64_t(tile_m) * TM;
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -62,12 +77,12 @@ sfb_f32_kernel(const float* __restrict__ U, int64_t ldu, const float* __restrict
 #pragma unroll
     for (int j = 0; j < NI_A; ++j) {
         const int f = (wave * NI_A + j) * 64 + lane;
-        voff_a[j] = static_cast<uint32_t>(((f / (TN / 4)) * ldu + n0 + (f % (TN / 4)) * 4) * 4);
+        voff_a[j] = static_cast<uint32_t>(((k_begin + f / (TN / 4)) * ldu + n0 + (f % (TN / 4)) * 4) * 4);
     }
 #pragma unroll
     for (int j = 0; j < NI_B; ++j) {
         const int f = (wave * NI_B + j) * 64 + lane;
-        voff_b[j] = static_cast<uint32_t>(((f / (TM / 4)) * ldv + m0 + (f % (TM / 4)) * 4) * 4);
+        voff_b[j] = static_cast<uint32_t>(((k_begin + f / (TM / 4)) * ldv + m0 + (f % (TM / 4)) * 4) * 4);
     }
     const uint32_t step_a = static_cast<uint32_t>(KT * ldu * 4), step_b = static_cast<uint32_t>(KT * ldv * 4);
     auto issue = [&](int t) {                    // stage t -> ring buffer t % NSTAGE; past K: zeros
@@ -118,7 +133,7 @@ sfb_f32_kernel(const float* __restrict__ U, int64_t ldu, const float* __restrict
     };
     auto interleave = [&]() { interleave_groups<8, 8 * BN>(); };
 
-    const int steps = (K + KT - 1) / KT;
+    const int steps = k_end > k_begin ? (k_end - k_begin + KT - 1) / KT : 0;
 #pragma unroll
     for (int t = 0; t < NSTAGE - 1; ++t) issue(t);
     wait_vmcnt<(NSTAGE - 2) * LPS>();
@@ -152,6 +167,16 @@ sfb_f32_kernel(const float* __restrict__ U, int64_t ldu, const float* __restrict
             const int64_t n = n0 + wn0 + BN * row + ta;
             if (n >= N) continue;
             const float d0 = acc[ta][0][r], d1 = acc[ta][1][r];
+            if constexpr (PART) {
+                float* dp = part + split * part_stride + n * int64_t(M) + mcol;
+                if (pair_ok && mcol + 1 < M) {
+                    *reinterpret_cast<float2*>(dp) = make_float2(d0, d1);
+                } else {
+                    if (mcol < M) dp[0] = d0;
+                    if (mcol + 1 < M) dp[1] = d1;
+                }
+                continue;
+            }
             float* wp = W + n * int64_t(M) + mcol;
             float* mp = Mom + n * int64_t(M) + mcol;
             if (pair_ok && mcol + 1 < M) {
@@ -180,35 +205,62 @@ sfb_f32_kernel(const float* __restrict__ U, int64_t ldu, const float* __restrict
 
 template <int BN>
 psd_status launch_f32(const float* U, int64_t ldu, const float* V, int64_t ldv, float* W, float* Mom,
-                      int64_t N, int64_t M, int64_t K, float lr, float mu, float wd, hipStream_t st)
+                      int64_t N, int64_t M, int64_t K, float lr, float mu, float wd, float* part, int splits,
+                      hipStream_t st)
 {
     constexpr int TN = 64 * BN;
     const int64_t tiles_n = (N + TN - 1) / TN, tiles_m = (M + TM - 1) / TM;
     const int64_t tiles = tiles_n * tiles_m;
-    if (tiles < 1 || tiles > 0x7fffffff) return PSD_E_INVALID;
+    if (tiles < 1 || tiles * splits > 0x7fffffff) return PSD_E_INVALID;
     // 32-bit byte offsets into each factor matrix, with room for the stages of read-ahead
     const int64_t u_bytes = K * ldu * 4, v_bytes = K * ldv * 4;
     const int64_t reach = (int64_t(1) << 32) - (NSTAGE + 2) * KT * (ldu > ldv ? ldu : ldv) * 4 - 4096;
     if (u_bytes > reach || v_bytes > reach) return PSD_E_UNSUPPORTED;
-    hipLaunchKernelGGL(sfb_f32_kernel<BN>, dim3(static_cast<uint32_t>(tiles)), dim3(THREADS), 0, st, U, ldu, V, ldv, W,
-                       Mom, static_cast<int>(N), static_cast<int>(M), static_cast<int>(K), lr, mu, wd,
-                       static_cast<int>(tiles_m), static_cast<uint32_t>(u_bytes), static_cast<uint32_t>(v_bytes));
+    const int64_t stages = (K + KT - 1) / KT;
+    const int sps = static_cast<int>((stages + splits - 1) / splits);
+    auto kern = splits > 1 ? sfb_f32_kernel<BN, true> : sfb_f32_kernel<BN, false>;
+    hipLaunchKernelGGL(kern, dim3(static_cast<uint32_t>(tiles * splits)), dim3(THREADS), 0, st, U, ldu, V, ldv, W, Mom,
+                       static_cast<int>(N), static_cast<int>(M), static_cast<int>(K), lr, mu, wd,
+                       static_cast<int>(tiles_m), static_cast<int>(tiles), static_cast<uint32_t>(u_bytes),
+                       static_cast<uint32_t>(v_bytes), part, sfb_part_stride(N, M), sps);
     PSD_HIP_TRY(hipGetLastError());
+    if (splits > 1) return launch_sfb_reduce(part, splits, N, M, W, Mom, lr, mu, wd, st);
     return PSD_OK;
+}
+
+// tile choice (and, with a workspace, the split of K) for one layer
+void choose_f32(int64_t N, int64_t M, int64_t K, bool may_split, int* bn, int* splits)
+{
+    // 128 x 128 tiles unless that leaves fewer than two workgroups per compute unit (one workgroup's
+    // four wavefronts cannot hide LDS and barrier latency on their own); with a workspace, few tiles
+    // are made up for by splitting K instead of by halving the tile
+    const int64_t slots = 2 * int64_t(device_cu_count());
+    const int64_t tiles128 = ((N + 127) / 128) * ((M + TM - 1) / TM);
+    const int forced = tune_value(PSD_TUNE_SFB_F32_TILE);
+    const int s128 = may_split ? sfb_splits_for(tiles128, slots, K) : 1;
+    if (forced == 1 || forced == 2) *bn = forced;
+    else *bn = (tiles128 < slots && s128 == 1) ? 1 : 2;
+    const int64_t tiles = ((N + 64 * *bn - 1) / (64 * *bn)) * ((M + TM - 1) / TM);
+    *splits = may_split ? sfb_splits_for(tiles, slots, K) : 1;
 }
 
 }  // namespace
 
-psd_status launch_sfb_f32(const float* U, int64_t ldu, const float* V, int64_t ldv, float* W, float* Mom,
-                          int64_t N, int64_t M, int64_t K, float lr, float mu, float wd, hipStream_t st)
+int sfb_f32_splits(int64_t N, int64_t M, int64_t K)
 {
-    // 128 x 128 tiles unless that leaves fewer than two workgroups per compute unit (one workgroup's
-    // four wavefronts cannot hide LDS and barrier latency on their own)
-    const int64_t tiles128 = ((N + 127) / 128) * ((M + TM - 1) / TM);
-    const int forced = tune_value(PSD_TUNE_SFB_F32_TILE);
-    const int bn = forced == 1 || forced == 2 ? forced : (tiles128 < 2 * int64_t(device_cu_count()) ? 1 : 2);
-    if (bn == 1) return launch_f32<1>(U, ldu, V, ldv, W, Mom, N, M, K, lr, mu, wd, st);
-    return launch_f32<2>(U, ldu, V, ldv, W, Mom, N, M, K, lr, mu, wd, st);
+    int bn, s;
+    choose_f32(N, M, K, true, &bn, &s);
+    return s;
+}
+
+psd_status launch_sfb_f32(const float* U, int64_t ldu, const float* V, int64_t ldv, float* W, float* Mom,
+                          int64_t N, int64_t M, int64_t K, float lr, float mu, float wd, float* part, int splits,
+                          hipStream_t st)
+{
+    int bn, s;
+    choose_f32(N, M, K, splits > 1, &bn, &s);
+    if (bn == 1) return launch_f32<1>(U, ldu, V, ldv, W, Mom, N, M, K, lr, mu, wd, part, splits, st);
+    return launch_f32<2>(U, ldu, V, ldv, W, Mom, N, M, K, lr, mu, wd, part, splits, st);
 }
 
 }  // namespace psd

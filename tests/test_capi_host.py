@@ -27,7 +27,7 @@ def test_library_exports_every_declared_symbol():
 def test_struct_layouts_match_the_header():
     assert ctypes.sizeof(psd.Plan) == 4 * 8 + 4 * 4 + 3 * 8
     assert ctypes.sizeof(psd.DenseSegment) == 8 + 4 + 4 + 3 * 8
-    assert ctypes.sizeof(psd.LayerTask) == ctypes.sizeof(psd.Plan) + 8 + 2 * 8 + 4 * 8 + 8 + 2 * 8 + 8 + 3 * 8
+    assert ctypes.sizeof(psd.LayerTask) == ctypes.sizeof(psd.Plan) + 8 + 2 * 8 + 4 * 8 + 8 + 2 * 8 + 2 * 8 + 8 + 3 * 8
 
 
 GRID = list(itertools.product([1, 3, 128, 256, 1000, 4096, 9216], [1, 2, 128, 1000, 4096, 21841],
@@ -111,15 +111,15 @@ def test_device_entry_points_reject_bad_arguments_before_launching():
     assert L.psd_pack_factors(pp, good, good, psd.BF16, U, 12, V, 8, None) == psd.E_INVALID    # ld*2 % 16
     assert L.psd_pack_factors(pp, good, good, psd.F32, _fake(0x10004), 8, V, 8, None) == psd.E_INVALID
     # sfb
-    assert L.psd_sync_fc_sfb(pp, psd.F32, U, 8, V, 8, None, Mom, 0.1, 0.9, 0.0, None) == psd.E_NULL
-    assert L.psd_sync_fc_sfb(pp, 9, U, 8, V, 8, W, Mom, 0.1, 0.9, 0.0, None) == psd.E_INVALID
-    assert L.psd_sync_fc_sfb(pp, psd.F32, U, 8, V, 8, W, W, 0.1, 0.9, 0.0, None) == psd.E_INVALID
-    assert L.psd_sync_fc_sfb(pp, psd.F32, U, 8, V, 8, _fake(0x30008), Mom, 0.1, 0.9, 0.0, None) == psd.E_INVALID
-    assert L.psd_sync_fc_sfb(pp, psd.BF16, U, 8, V, 7, W, Mom, 0.1, 0.9, 0.0, None) == psd.E_INVALID
+    assert L.psd_sync_fc_sfb(pp, psd.F32, U, 8, V, 8, None, Mom, 0.1, 0.9, 0.0, None, 0, None) == psd.E_NULL
+    assert L.psd_sync_fc_sfb(pp, 9, U, 8, V, 8, W, Mom, 0.1, 0.9, 0.0, None, 0, None) == psd.E_INVALID
+    assert L.psd_sync_fc_sfb(pp, psd.F32, U, 8, V, 8, W, W, 0.1, 0.9, 0.0, None, 0, None) == psd.E_INVALID
+    assert L.psd_sync_fc_sfb(pp, psd.F32, U, 8, V, 8, _fake(0x30008), Mom, 0.1, 0.9, 0.0, None, 0, None) == psd.E_INVALID
+    assert L.psd_sync_fc_sfb(pp, psd.BF16, U, 8, V, 7, W, Mom, 0.1, 0.9, 0.0, None, 0, None) == psd.E_INVALID
     bad = psd.Plan()
     ctypes.memmove(ctypes.byref(bad), ctypes.byref(plan), ctypes.sizeof(plan))
     bad.P = 0
-    assert L.psd_sync_fc_sfb(ctypes.byref(bad), psd.F32, U, 8, V, 8, W, Mom, 0.1, 0.9, 0.0, None) == psd.E_INVALID
+    assert L.psd_sync_fc_sfb(ctypes.byref(bad), psd.F32, U, 8, V, 8, W, Mom, 0.1, 0.9, 0.0, None, 0, None) == psd.E_INVALID
     # bias
     assert L.psd_sync_fc_bias(pp, psd.F32, U, 8, None, Mom, 0.1, 0.9, 0.0, None) == psd.E_NULL
     assert L.psd_sync_fc_bias(pp, psd.F32, U, 8, W, W, 0.1, 0.9, 0.0, None) == psd.E_INVALID
@@ -138,7 +138,7 @@ def test_device_entry_points_reject_bad_arguments_before_launching():
     assert L.psd_sync_dense_ps(0, 2, good, W, Mom, 0.1, 0.9, 0.0, 1, None) == psd.OK              # empty layer: no-op
     assert L.psd_sync_dense_ps(16, 2, good, W, Mom, 0.1, 0.9, -1e-4, 1, None) == psd.E_INVALID     # negative weight decay
     assert L.psd_sync_dense_ps(16, 2, good, W, Mom, 0.1, 0.9, float('nan'), 1, None) == psd.E_INVALID
-    assert L.psd_sync_fc_sfb(pp, psd.F32, U, 8, V, 8, W, Mom, 0.1, 0.9, -1.0, None) == psd.E_INVALID
+    assert L.psd_sync_fc_sfb(pp, psd.F32, U, 8, V, 8, W, Mom, 0.1, 0.9, -1.0, None, 0, None) == psd.E_INVALID
     # multi
     seg = (psd.DenseSegment * 1)()
     seg[0].n, seg[0].P, seg[0].S = 16, 2, 1
@@ -172,11 +172,11 @@ def test_sizes_beyond_what_the_kernels_index_are_refused_before_launching():
     assert L.psd_pack_factors(ctypes.byref(plan), ptrs, ptrs, psd.F32, U, 8, V, 8, None) == psd.E_UNSUPPORTED
     # the reconstruct kernels use 32-bit byte offsets into each stacked factor matrix
     plan = psd.plan_layer(psd.LAYER_FC, 8, 2 ** 21, 256, 8)          # U: 2048 x 2^21 bf16 = 8.6 GB
-    assert L.psd_sync_fc_sfb(ctypes.byref(plan), psd.BF16, U, 2 ** 21, V, 8, W, Mom, 0.1, 0.9, 0.0, None) == psd.E_UNSUPPORTED
-    assert L.psd_sync_fc_sfb(ctypes.byref(plan), psd.F32, U, 2 ** 21, V, 8, W, Mom, 0.1, 0.9, 0.0, None) == psd.E_UNSUPPORTED
+    assert L.psd_sync_fc_sfb(ctypes.byref(plan), psd.BF16, U, 2 ** 21, V, 8, W, Mom, 0.1, 0.9, 0.0, None, 0, None) == psd.E_UNSUPPORTED
+    assert L.psd_sync_fc_sfb(ctypes.byref(plan), psd.F32, U, 2 ** 21, V, 8, W, Mom, 0.1, 0.9, 0.0, None, 0, None) == psd.E_UNSUPPORTED
     # M, N, K beyond 2^31 are invalid for the device entry points (the plan itself is fine)
     plan = psd.plan_layer(psd.LAYER_FC, 2 ** 31, 8, 1, 1)
-    assert L.psd_sync_fc_sfb(ctypes.byref(plan), psd.F32, U, 8, V, 2 ** 31, W, Mom, 0.1, 0.9, 0.0, None) == psd.E_INVALID
+    assert L.psd_sync_fc_sfb(ctypes.byref(plan), psd.F32, U, 8, V, 2 ** 31, W, Mom, 0.1, 0.9, 0.0, None, 0, None) == psd.E_INVALID
 
 
 def test_binding_fails_loudly_without_the_library(monkeypatch):
@@ -208,5 +208,31 @@ def test_factor_matrices_past_the_32_bit_offset_reach_are_refused_on_the_host():
     for dtype in (psd.BF16, psd.F32):
         ldu, ldv = psd.factor_ld(big.N, dtype), psd.factor_ld(big.M, dtype)
         st = L.psd_sync_fc_sfb(ctypes.byref(big), dtype, fake, ldu, fake, ldv, fake, ctypes.c_void_p(0x20000000),
-                               0.01, 0.9, 0.0, None)
+                               0.01, 0.9, 0.0, None, 0, None)
         assert st == psd.E_UNSUPPORTED, (dtype, st)
+
+
+def test_workspace_query_and_argument_checks():
+    """psd_sfb_workspace_bytes is host logic: a layer that leaves most compute units without a tile asks
+    for 2-4 partial dW matrices, a layer with a tile per compute unit or more for none; a workspace that
+    is too small, misaligned or NULL with a non-zero size is refused before anything is launched."""
+    L = psd.lib()
+    fake = lambda a: ctypes.c_void_p(a)
+    small = psd.plan_layer(psd.LAYER_FC, 1024, 1000, 256, 8)      # 64 tiles of 128 x 128
+    fc8 = psd.plan_layer(psd.LAYER_FC, 4096, 1000, 256, 8)        # 256 tiles: one per compute unit already
+    fc6 = psd.plan_layer(psd.LAYER_FC, 9216, 4096, 256, 8)
+    tiny = psd.plan_layer(psd.LAYER_FC, 256, 128, 32, 4)          # K = 128: too short to split
+    for dtype in (psd.BF16, psd.F32):
+        need = psd.sfb_workspace_bytes(small, dtype)
+        per = (1000 * 1024 + 3) // 4 * 4 * 4
+        assert need % per == 0 and 2 <= need // per <= 4 and need % 16 == 0, (dtype, need)
+        for plan in (fc8, fc6, tiny):
+            assert psd.sfb_workspace_bytes(plan, dtype) == 0
+        ldu, ldv = psd.factor_ld(small.N, dtype), psd.factor_ld(small.M, dtype)
+        args = (ctypes.byref(small), dtype, fake(0x10000000), ldu, fake(0x20000000), ldv, fake(0x30000000),
+                fake(0x40000000), 0.01, 0.9, 0.0)
+        assert L.psd_sync_fc_sfb(*args, fake(0x50000000), need - 16, None) == psd.E_WORKSPACE
+        assert L.psd_sync_fc_sfb(*args, None, need, None) == psd.E_NULL
+        assert L.psd_sync_fc_sfb(*args, fake(0x50000008), need, None) == psd.E_INVALID
+    assert L.psd_sfb_workspace_bytes(None, psd.BF16) == 0 and L.psd_sfb_workspace_bytes(ctypes.byref(small), 7) == 0
+    assert b"workspace" in L.psd_status_string(psd.E_WORKSPACE)

@@ -246,6 +246,63 @@ def test_weight_decay_gaussian_within_tolerance():
         assert max(e) <= TOL_F32, (name, e)
 
 
+SPLIT_SHAPES = [  # M, N, B, P: few output tiles and K >= 1024, so that a workspace makes the kernels split K
+    (1024, 1000, 256, 8),      # GoogLeNet-sized classifier at batch 256 per worker: 64 tiles, split in four
+    (520, 300, 220, 5),        # ragged tiles both ways, K = 1100: ragged last stage and uneven splits
+    (521, 130, 128, 9),        # rows of W not 16-byte aligned (element-wise epilogue), K = 1152
+    (128, 128, 512, 4),        # a single tile, K = 2048: the deepest split
+]
+
+
+@pytest.mark.parametrize("M,N,B,P", SPLIT_SHAPES)
+@pytest.mark.parametrize("dtype", [psd.F32, psd.BF16])
+def test_sfb_split_k_with_workspace_bit_exact_and_equal_to_unsplit(M, N, B, P, dtype):
+    """With a workspace the sum over k is split over several workgroups per tile and finished by the
+    parameter-server sum kernel.  Integer-valued factors: bit-exact against the oracle; Gaussian factors:
+    within tolerance of the oracle and of the unsplit kernel."""
+    d = inputs.fc_layer_integer(M, N, B, P, seed=M + 3 * N)
+    plan, U, ldu, V, ldv = run_pack(d, dtype)
+    ws = psd.alloc_workspace(plan, dtype, DEV)
+    assert ws is not None and 2 <= ws.numel() * 4 // ((N * M + 3) // 4 * 16) <= 4
+    ws.fill_(float("nan"))                                 # stale contents must not matter
+    W, Mom = dev(d["W"]), dev(d["Mom"])
+    psd.sync_fc_sfb(plan, dtype, U, ldu, V, ldv, W, Mom, 0.25, 0.5, wd=0.25, workspace=ws)
+    torch.cuda.synchronize()
+    Uo, Vo = orc.pack_factors(d["delta"], d["act"])
+    Wr, Mr = orc.sync_fc_sfb(Uo, Vo, d["W"], d["Mom"], 0.25, 0.5, wd=0.25)
+    assert np.array_equal(Mom.cpu().numpy(), Mr), np.argwhere(Mom.cpu().numpy() != Mr)[:8]
+    assert np.array_equal(W.cpu().numpy(), Wr)
+
+    g = inputs.fc_layer(M, N, B, P, seed=M + N, mom_std=1e-4)
+    plan, U, ldu, V, ldv = run_pack(g, dtype)
+    name = "f32" if dtype == psd.F32 else "bf16"
+    Uo, Vo = orc.pack_factors(g["delta"], g["act"], name)
+    Wr, Mr = orc.sync_fc_sfb(Uo, Vo, g["W"], g["Mom"], inputs.LR, inputs.MU)
+    outs = []
+    for workspace in (ws, None):
+        W, Mom = dev(g["W"]), dev(g["Mom"])
+        psd.sync_fc_sfb(plan, dtype, U, ldu, V, ldv, W, Mom, inputs.LR, inputs.MU, workspace=workspace)
+        torch.cuda.synchronize()
+        e = three_errors(g["W"], W.cpu().numpy(), Mom.cpu().numpy(), Wr, Mr)
+        assert max(e) <= TOL_F32, (workspace is not None, e)
+        outs.append(Mom.cpu().numpy())
+    assert orc.rel_frob(outs[0], outs[1]) <= TOL_F32
+
+
+def test_sfb_workspace_is_ignored_by_layers_that_fill_the_gpu():
+    d = inputs.fc_layer_integer(2048, 2048, 8, 4, seed=12)      # 256 tiles of 128 x 128 ... K = 32: no split either way
+    plan, U, ldu, V, ldv = run_pack(d, psd.BF16)
+    assert psd.sfb_workspace_bytes(plan, psd.BF16) == 0
+    spare = torch.full((1024,), float("nan"), device=DEV)
+    W, Mom = dev(d["W"]), dev(d["Mom"])
+    psd.sync_fc_sfb(plan, psd.BF16, U, ldu, V, ldv, W, Mom, 0.25, 0.5, workspace=spare)
+    torch.cuda.synchronize()
+    Uo, Vo = orc.pack_factors(d["delta"], d["act"])
+    Wr, Mr = orc.sync_fc_sfb(Uo, Vo, d["W"], d["Mom"], 0.25, 0.5)
+    assert np.array_equal(Mom.cpu().numpy(), Mr) and np.array_equal(W.cpu().numpy(), Wr)
+    assert torch.isnan(spare).all()                              # untouched
+
+
 def _random_shapes(count, seed):
     rng = np.random.default_rng(seed)
     out = []
