@@ -123,6 +123,22 @@ psd_status psd_sync_fc_sfb(const psd_plan* plan, int32_t factor_dtype,
  * depends on the layer shape, the factor dtype, the current device's CU count and the pinned tile. */
 size_t psd_sfb_workspace_bytes(const psd_plan* plan, int32_t factor_dtype);
 
+/* psd_sync_fc_sfb for callers that cannot allocate and have no workspace to pass: code under HIP graph
+ * capture, tight serving loops, harnesses that forbid hipMalloc.  Same arguments and arithmetic as
+ * psd_sync_fc_sfb called with a workspace of exactly psd_sfb_workspace_bytes() bytes, but the partial
+ * tiles of a split layer go to a fixed PSD_STATIC_SCRATCH_BYTES array that lives in the library's device
+ * code (each GPU the library runs on holds its own copy until the process ends).  Calls no allocating
+ * routine.  A layer whose split needs more than PSD_STATIC_SCRATCH_BYTES is refused with
+ * PSD_E_WORKSPACE (use psd_sync_fc_sfb with your own workspace, or none); a layer that is not split
+ * needs no scratch and runs as psd_sync_fc_sfb without a workspace.  All calls on one GPU share that
+ * GPU's array: calls that overlap in time on one GPU (different streams, different threads) race on it
+ * and must be serialised by the caller.  The array keeps the last call's partials; nothing has to be
+ * cleared between calls. */
+#define PSD_STATIC_SCRATCH_BYTES (16u << 20)
+psd_status psd_sync_fc_sfb_static(const psd_plan* plan, int32_t factor_dtype,
+                                  const void* U, int64_t ldu, const void* V, int64_t ldv,
+                                  float* W, float* Mom, float lr, float mu, float wd, void* stream);
+
 /* Bias of an FC layer under SFB.  For z = W a + b the per-sample gradient w.r.t. b is the error
  * vector itself (the chain rule behind Eq. 5), so with the stacked errors U of the layer
  *     db[n] = sum_{k<K} U[k][n] ;  mom_bias <- mu*mom_bias + lr*(db + wd*bias) ;  bias <- bias - mom_bias.

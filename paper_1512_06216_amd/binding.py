@@ -22,6 +22,7 @@ F32, BF16 = 0, 1
 TUNE_SFB_BF16_TILE, TUNE_SFB_F32_TILE = 0, 1
 ROUTE_NAMES = {ROUTE_PS_DENSE: "PS_DENSE", ROUTE_SFB: "SFB", ROUTE_SF_PS: "SF_PS"}
 MAX_WORKERS, MAX_MULTI_SEGMENTS, MAX_MULTI_WORKERS = 64, 16, 16
+STATIC_SCRATCH_BYTES = 16 << 20
 
 _f32p = ctypes.POINTER(ctypes.c_float)
 _f32pp = ctypes.POINTER(_f32p)
@@ -78,6 +79,9 @@ SIGNATURES = {
                                          ctypes.c_float, ctypes.c_float, ctypes.c_float, ctypes.c_void_p,
                                          ctypes.c_size_t, ctypes.c_void_p]),
     "psd_sfb_workspace_bytes": (ctypes.c_size_t, [ctypes.POINTER(Plan), ctypes.c_int32]),
+    "psd_sync_fc_sfb_static": (ctypes.c_int32, [ctypes.POINTER(Plan), ctypes.c_int32, ctypes.c_void_p, ctypes.c_int64,
+                                                ctypes.c_void_p, ctypes.c_int64, ctypes.c_void_p, ctypes.c_void_p,
+                                                ctypes.c_float, ctypes.c_float, ctypes.c_float, ctypes.c_void_p]),
     "psd_sync_fc_bias": (ctypes.c_int32, [ctypes.POINTER(Plan), ctypes.c_int32, ctypes.c_void_p, ctypes.c_int64,
                                           ctypes.c_void_p, ctypes.c_void_p, ctypes.c_float, ctypes.c_float,
                                           ctypes.c_float, ctypes.c_void_p]),
@@ -217,6 +221,16 @@ def sync_fc_sfb(plan, factor_dtype, U, ldu, V, ldv, W, Mom, lr, mu, stream=None,
     ws, ws_bytes = _workspace_args(workspace)
     _check(lib().psd_sync_fc_sfb(ctypes.byref(plan), factor_dtype, up, ldu, vp, ldv, wp, mp, lr, mu, wd,
                                  ws, ws_bytes, _stream_handle(stream)), "psd_sync_fc_sfb")
+
+
+def sync_fc_sfb_static(plan, factor_dtype, U, ldu, V, ldv, W, Mom, lr, mu, stream=None, wd=0.0):
+    """sync_fc_sfb on the library's own fixed scratch array (allocates nothing)."""
+    up = _dev_ptr(U, _FACTOR_TORCH.get(factor_dtype, ()), plan.K * ldu, "U")
+    vp = _dev_ptr(V, _FACTOR_TORCH.get(factor_dtype, ()), plan.K * ldv, "V")
+    wp = _dev_ptr(W, torch.float32, plan.N * plan.M, "W")
+    mp = _dev_ptr(Mom, torch.float32, plan.N * plan.M, "Mom")
+    _check(lib().psd_sync_fc_sfb_static(ctypes.byref(plan), factor_dtype, up, ldu, vp, ldv, wp, mp, lr, mu, wd,
+                                        _stream_handle(stream)), "psd_sync_fc_sfb_static")
 
 
 def sync_fc_bias(plan, factor_dtype, U, ldu, bias, mom_bias, lr, mu, stream=None, wd=0.0):
