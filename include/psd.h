@@ -202,8 +202,14 @@ typedef struct psd_layer_task {
  * (layers[0] is the lowest layer) and issued top-down, layer L-1 first, each on its own
  * stream as if its gradient had just been produced by backpropagation.  Each layer follows
  * the route its plan holds under `rule`: PS_DENSE -> psd_sync_dense_ps; SFB or SF_PS ->
- * psd_pack_factors then psd_sync_fc_sfb.  Layers own disjoint parameters (Section 4.2), so
- * no ordering between streams is needed; the caller synchronises the streams.
+ * psd_pack_factors then psd_sync_fc_sfb (with the layer's workspace, if any).  Layers own disjoint
+ * parameters (Section 4.2), so no ordering between streams is needed; the caller synchronises the
+ * streams.
+ * Consecutive PS_DENSE layers WITHOUT ev_ready (their gradients exist already, so nothing is gained
+ * by issuing them one by one) with at most PSD_MAX_MULTI_WORKERS copies are summed by ONE
+ * psd_sync_dense_ps_multi launch on the stream of the topmost of them (up to PSD_MAX_MULTI_SEGMENTS
+ * per launch); the streams of the other layers of the group are made to wait for that launch, and
+ * every group member's ev_begin / ev_end are recorded around it.
  * Stops at and returns the first error. */
 psd_status psd_sync_iteration(int32_t L, const psd_layer_task* layers, float lr, float mu, float wd,
                               int32_t rule);

@@ -146,13 +146,13 @@ psd_status psd_pack_factors(const psd_plan* plan, const float* const* delta_p, c
     PackArgs a;
     a.P = static_cast<int32_t>(plan->P);
     a.B = plan->B;
-    for (int p = 0; p < PSD_MAX_WORKERS; ++p) a.src[p] = p < a.P ? delta_p[p] : nullptr;
-    a.dst = U; a.cols = plan->N; a.ld = ldu;
-    psd_status r = launch_pack(a, out_dtype, st);
-    if (r != PSD_OK) return r;
-    for (int p = 0; p < PSD_MAX_WORKERS; ++p) a.src[p] = p < a.P ? act_p[p] : nullptr;
-    a.dst = V; a.cols = plan->M; a.ld = ldv;
-    return launch_pack(a, out_dtype, st);
+    for (int p = 0; p < PSD_MAX_WORKERS; ++p) {
+        a.u.src[p] = p < a.P ? delta_p[p] : nullptr;
+        a.v.src[p] = p < a.P ? act_p[p] : nullptr;
+    }
+    a.u.dst = U; a.u.cols = plan->N; a.u.ld = ldu;
+    a.v.dst = V; a.v.cols = plan->M; a.v.ld = ldv;
+    return launch_pack(a, out_dtype, st);          // one launch stacks both matrices
 }
 
 size_t psd_sfb_workspace_bytes(const psd_plan* plan, int32_t factor_dtype)
@@ -262,6 +262,26 @@ psd_status psd_sync_dense_ps_multi(int32_t L, const psd_dense_segment* segs, flo
     return launch_dense_table(t, static_cast<int32_t>(blocks), lr, mu, wd, static_cast<hipStream_t>(stream));
 }
 
+namespace {
+
+// One event per host thread that orders the other streams of a fused parameter-server group after the
+// group's single launch (created on first use, never destroyed; holds no device memory).
+psd_status fuse_event(hipEvent_t* out)
+{
+    static thread_local hipEvent_t ev = nullptr;
+    if (!ev) PSD_HIP_TRY(hipEventCreateWithFlags(&ev, hipEventDisableTiming));
+    *out = ev;
+    return PSD_OK;
+}
+
+bool fusable_ps_layer(const psd_layer_task& t, int32_t rule)
+{
+    const int32_t route = rule == PSD_RULE_ALG3 ? t.plan.route_alg3 : t.plan.route_vs_dense;
+    return route == PSD_ROUTE_PS_DENSE && !t.ev_ready && t.G && t.plan.P <= PSD_MAX_MULTI_WORKERS;
+}
+
+}  // namespace
+
 // Algorithm 2's order: the top layer's gradient exists first, so its synchronisation is
 // issued first; every layer goes to its own stream.
 psd_status psd_sync_iteration(int32_t L, const psd_layer_task* layers, float lr, float mu, float wd, int32_t rule)
@@ -272,6 +292,46 @@ psd_status psd_sync_iteration(int32_t L, const psd_layer_task* layers, float lr,
         const psd_layer_task& t = layers[l];
         const int32_t route = rule == PSD_RULE_ALG3 ? t.plan.route_alg3 : t.plan.route_vs_dense;
         hipStream_t st = static_cast<hipStream_t>(t.stream);
+
+        // A run of parameter-server layers whose gradients all exist already (no ev_ready) gains nothing
+        // from being issued one by one: their sums go into ONE launch on the top layer's stream, and the
+        // other layers' streams are ordered after it.
+        int32_t lo = l;
+        if (fusable_ps_layer(t, rule))
+            while (lo > 0 && l - lo + 1 < PSD_MAX_MULTI_SEGMENTS && fusable_ps_layer(layers[lo - 1], rule)) --lo;
+        if (lo < l) {
+            psd_dense_segment segs[PSD_MAX_MULTI_SEGMENTS];
+            for (int32_t j = l; j >= lo; --j) {
+                const psd_layer_task& u = layers[j];
+                uint64_t n;
+                if (mul_u64(static_cast<uint64_t>(u.plan.M), static_cast<uint64_t>(u.plan.N), &n) || n > (uint64_t(1) << 40))
+                    return PSD_E_INVALID;
+                psd_dense_segment& sg = segs[l - j];
+                sg.n = static_cast<int64_t>(n); sg.P = static_cast<int32_t>(u.plan.P); sg.S = u.S;
+                sg.G = u.G; sg.W = u.W; sg.Mom = u.Mom;
+                if (u.ev_begin) PSD_HIP_TRY(hipEventRecord(static_cast<hipEvent_t>(u.ev_begin), st));
+            }
+            const psd_status r = psd_sync_dense_ps_multi(l - lo + 1, segs, lr, mu, wd, t.stream);
+            if (r != PSD_OK) return r;
+            hipEvent_t done = nullptr;
+            bool other_streams = false;
+            for (int32_t j = l; j >= lo; --j) {
+                const psd_layer_task& u = layers[j];
+                if (u.ev_end) PSD_HIP_TRY(hipEventRecord(static_cast<hipEvent_t>(u.ev_end), st));
+                other_streams = other_streams || u.stream != t.stream;
+            }
+            if (other_streams) {
+                const psd_status e = fuse_event(&done);
+                if (e != PSD_OK) return e;
+                PSD_HIP_TRY(hipEventRecord(done, st));
+                for (int32_t j = l - 1; j >= lo; --j)
+                    if (layers[j].stream != t.stream)
+                        PSD_HIP_TRY(hipStreamWaitEvent(static_cast<hipStream_t>(layers[j].stream), done, 0));
+            }
+            l = lo;               // the loop's --l moves below the group
+            continue;
+        }
+
         if (t.ev_ready) PSD_HIP_TRY(hipStreamWaitEvent(st, static_cast<hipEvent_t>(t.ev_ready), 0));
         psd_status r;
         if (route == PSD_ROUTE_PS_DENSE) {

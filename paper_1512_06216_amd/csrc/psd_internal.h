@@ -52,13 +52,18 @@ psd_status launch_dense_table(const DenseTable& t, int32_t total_blocks, float l
 psd_status launch_dense_wide(const DenseWide& a, float lr, float mu, float wd, hipStream_t st);
 int32_t dense_chunks_for(int64_t n, int32_t S);   // workgroups per shard
 
-struct PackArgs {
+struct PackSide {            // one of the two stacked matrices of a layer
     const float* src[PSD_MAX_WORKERS];
     void* dst;
-    int64_t cols, ld, B;
-    int32_t P;
+    int64_t cols, ld;
 };
-psd_status launch_pack(const PackArgs& a, int32_t out_dtype, hipStream_t st);
+struct PackArgs {
+    PackSide u, v;           // errors (B x N blocks -> K x ldu), activations (B x M blocks -> K x ldv)
+    int64_t B;
+    int32_t P;
+    int32_t bx_u;            // workgroup columns serving u (filled in by launch_pack)
+};
+psd_status launch_pack(PackArgs& a, int32_t out_dtype, hipStream_t st);
 
 // ---- reconstruction.  part / splits: with splits > 1 the contraction is split over `splits`
 // workgroups per tile, each storing a partial dW (N x M, sfb_part_stride apart) to `part`, and the

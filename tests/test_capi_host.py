@@ -164,12 +164,7 @@ def test_device_entry_points_reject_bad_arguments_before_launching():
 
 def test_sizes_beyond_what_the_kernels_index_are_refused_before_launching():
     L = psd.lib()
-    f32p = ctypes.POINTER(ctypes.c_float)
     U, V, W, Mom = _fake(0x10000), _fake(0x20000), _fake(0x30000), _fake(0x40000)
-    # pack uses one grid row per stacked sample: K = P*B > 65535 is not served
-    plan = psd.plan_layer(psd.LAYER_FC, 8, 8, 2048, 64)
-    ptrs = (f32p * 64)(*[ctypes.cast(0x1000 * (i + 1), f32p) for i in range(64)])
-    assert L.psd_pack_factors(ctypes.byref(plan), ptrs, ptrs, psd.F32, U, 8, V, 8, None) == psd.E_UNSUPPORTED
     # the reconstruct kernels use 32-bit byte offsets into each stacked factor matrix
     plan = psd.plan_layer(psd.LAYER_FC, 8, 2 ** 21, 256, 8)          # U: 2048 x 2^21 bf16 = 8.6 GB
     assert L.psd_sync_fc_sfb(ctypes.byref(plan), psd.BF16, U, 2 ** 21, V, 8, W, Mom, 0.1, 0.9, 0.0, None, 0, None) == psd.E_UNSUPPORTED

@@ -638,6 +638,39 @@ def test_iteration_waits_for_the_layers_gradient_event():
     hip.hipEventDestroy(ev_conv)
 
 
+def test_iteration_fused_parameter_server_launch_orders_every_layers_stream():
+    """Conv layers without a readiness event are summed by one launch on the top conv layer's stream; work
+    a caller then enqueues on ANY of those layers' own streams must see that layer updated."""
+    sizes = [70001, 300000, 1234567, 5]
+    layers = [inputs.dense_layer_integer(n, 8, seed=300 + i) for i, n in enumerate(sizes)]
+    streams = [torch.cuda.Stream(device=DEV) for _ in layers]
+    tasks, state = [], []
+    for d, st in zip(layers, streams):
+        plan = psd.plan_layer(psd.LAYER_CONV, d["n"], 1, 16, d["P"])
+        W, Mom = dev(d["W"]), dev(d["Mom"])
+        tasks.append(dict(plan=plan, G=[dev(g) for g in d["G"]], S=min(8, d["n"]), W=W, Mom=Mom, stream=st))
+        state.append((W, Mom))
+    torch.cuda.synchronize()
+    psd.Iteration(tasks).run(0.25, 0.5, psd.RULE_ALG3, wd=0.5)
+    seen = []
+    for (W, Mom), st in zip(state, streams):
+        with torch.cuda.stream(st):                    # no device-wide synchronisation in between
+            seen.append((W.clone(), Mom.clone()))
+    for st in streams:
+        st.synchronize()
+    for d, (Wc, Mc) in zip(layers, seen):
+        Wr, Mr = orc.sync_dense_ps(d["G"], d["W"], d["Mom"], 0.25, 0.5, min(8, d["n"]), wd=0.5)
+        assert np.array_equal(Wc.cpu().numpy(), Wr) and np.array_equal(Mc.cpu().numpy(), Mr), d["n"]
+
+
+def test_pack_more_rows_than_one_grid_dimension_holds():
+    # K = P*B = 70 000 stacked samples: the pack kernel's row index wraps around its grid
+    d = inputs.fc_layer_integer(8, 4, 1094, 64, seed=70)
+    plan, U, ldu, V, ldv = run_pack(d, psd.BF16)
+    Uo, Vo = orc.pack_factors(d["delta"], d["act"], "bf16")
+    assert np.array_equal(bits16(U)[:, :4], Uo) and np.array_equal(bits16(V)[:, :8], Vo)
+
+
 def test_iteration_routes_follow_the_plan():
     # fc8-shaped layer at P=8, B=256: Algorithm 3 says SF_PS, the prose rule says SFB; both
     # run the reconstruction.  A layer whose route is PS_DENSE but has no dense copies is refused.
