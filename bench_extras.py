@@ -9,18 +9,28 @@ PEAK_HBM_GBS = 8000.0
 PEAK_TF = {"bf16": 2500.0, "f32": 157.3}
 
 
-def _time_ms(torch, fn, n_sets, iters=20, warmup=3):
-    """Mean milliseconds per call of fn(set_index), rotating over n_sets buffer sets."""
-    for i in range(warmup):
+def _time_ms(torch, fn, n_sets, iters=20, warmup_ms=100.0, batches=5):
+    """Median over `batches` of the mean milliseconds per call of fn(set_index), rotating over n_sets
+    buffer sets, after at least warmup_ms of the same calls (an idle GPU's clocks take ~0.1 s to settle)."""
+    import time
+    t0 = time.perf_counter()
+    i = 0
+    while (time.perf_counter() - t0) * 1e3 < warmup_ms:
         fn(i % n_sets)
+        i += 1
+        if i % 16 == 0:
+            torch.cuda.synchronize()
     torch.cuda.synchronize()
-    a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-    a.record()
-    for i in range(iters):
-        fn(i % n_sets)
-    b.record()
-    torch.cuda.synchronize()
-    return a.elapsed_time(b) / iters
+    ts = []
+    for _ in range(batches):
+        a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        a.record()
+        for i in range(iters):
+            fn(i % n_sets)
+        b.record()
+        torch.cuda.synchronize()
+        ts.append(a.elapsed_time(b) / iters)
+    return float(np.median(ts))
 
 
 def fc_config(psd, inputs, torch, dev, cfg_id, dtype_name=None, working_set_mb=600):
@@ -45,9 +55,12 @@ def fc_config(psd, inputs, torch, dev, cfg_id, dtype_name=None, working_set_mb=6
         s = sets[i]
         psd.pack_factors(plan, s["delta"], s["act"], dtype, s["U"], s["ldu"], s["V"], s["ldv"])
 
+    ws = psd.alloc_workspace(plan, dtype, dev)
+
     def sfb(i):
         s = sets[i]
-        psd.sync_fc_sfb(plan, dtype, s["U"], s["ldu"], s["V"], s["ldv"], s["W"], s["Mom"], inputs.LR, inputs.MU)
+        psd.sync_fc_sfb(plan, dtype, s["U"], s["ldu"], s["V"], s["ldv"], s["W"], s["Mom"], inputs.LR, inputs.MU,
+                        workspace=ws)
 
     def both(i):
         pack(i)

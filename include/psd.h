@@ -205,8 +205,9 @@ typedef struct psd_layer_task {
  * psd_pack_factors then psd_sync_fc_sfb (with the layer's workspace, if any).  Layers own disjoint
  * parameters (Section 4.2), so no ordering between streams is needed; the caller synchronises the
  * streams.
- * Consecutive PS_DENSE layers WITHOUT ev_ready (their gradients exist already, so nothing is gained
- * by issuing them one by one) with at most PSD_MAX_MULTI_WORKERS copies are summed by ONE
+ * Consecutive PS_DENSE layers whose gradients become available together (none has an ev_ready, or all
+ * name the same event), so that nothing is gained by issuing them one by one, with at most
+ * PSD_MAX_MULTI_WORKERS copies, are summed by ONE
  * psd_sync_dense_ps_multi launch on the stream of the topmost of them (up to PSD_MAX_MULTI_SEGMENTS
  * per launch); the streams of the other layers of the group are made to wait for that launch, and
  * every group member's ev_begin / ev_end are recorded around it.
@@ -214,12 +215,13 @@ typedef struct psd_layer_task {
 psd_status psd_sync_iteration(int32_t L, const psd_layer_task* layers, float lr, float mu, float wd,
                               int32_t rule);
 
-/* Tuning / test hook (not part of the method): pins the workgroup tile the reconstruction kernels
- * use instead of letting the library pick one from the layer shape.  Process-wide, takes effect on
- * the next launch; value -1 restores the automatic choice; any other value outside the listed range is
- * refused with PSD_E_INVALID and changes nothing.  Results never depend on the tile (only speed does).
- *   PSD_TUNE_SFB_BF16_TILE: 0 = 128 x 256, 1 = 128 x 192, 2 = 128 x 128 (rows n x columns m of W)
- *   PSD_TUNE_SFB_F32_TILE:  1 = 64 x 128,  2 = 128 x 128 */
+/* Tuning / test hook (not part of the method): pins a choice the library otherwise makes itself.
+ * Process-wide, takes effect on the next call; value -1 restores the automatic choice; any other value
+ * outside the listed range is refused with PSD_E_INVALID and changes nothing.  Results never depend on
+ * these choices (only speed does).
+ *   PSD_TUNE_SFB_BF16_TILE: workgroup tile of the bf16 reconstruction, rows n x columns m of W:
+ *                           0 = 128 x 256, 1 = 128 x 192, 2 = 128 x 128
+ *   PSD_TUNE_SFB_F32_TILE:  ... of the fp32 reconstruction: 1 = 64 x 128, 2 = 128 x 128 */
 enum { PSD_TUNE_SFB_BF16_TILE = 0, PSD_TUNE_SFB_F32_TILE = 1, PSD_TUNE_COUNT_ = 2 };
 psd_status psd_tune_set(int32_t knob, int32_t value);
 

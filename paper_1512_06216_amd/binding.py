@@ -250,20 +250,30 @@ def sync_dense_ps(G, W, Mom, lr, mu, S, stream=None, wd=0.0):
            "psd_sync_dense_ps")
 
 
+class DenseMulti:
+    """Marshalled, reusable argument block for psd_sync_dense_ps_multi.  layers: list of (G_list, W, Mom, S)."""
+
+    def __init__(self, layers):
+        self.segs = (DenseSegment * len(layers))()
+        self._keep = []
+        for i, (G, W, Mom, S) in enumerate(layers):
+            n = W.numel()
+            g = _ptr_array(G, n, "G")
+            self._keep.append(g)
+            self.segs[i].n, self.segs[i].P, self.segs[i].S = n, len(G), S
+            self.segs[i].G = ctypes.cast(g, _f32pp)
+            self.segs[i].W = ctypes.cast(_dev_ptr(W, torch.float32, n, "W"), _f32p)
+            self.segs[i].Mom = ctypes.cast(_dev_ptr(Mom, torch.float32, n, "Mom"), _f32p)
+        self.L = len(layers)
+
+    def run(self, lr, mu, stream=None, wd=0.0):
+        _check(lib().psd_sync_dense_ps_multi(self.L, self.segs, lr, mu, wd, _stream_handle(stream)),
+               "psd_sync_dense_ps_multi")
+
+
 def sync_dense_ps_multi(layers, lr, mu, stream=None, wd=0.0):
     """layers: list of (G_list, W, Mom, S)."""
-    segs = (DenseSegment * len(layers))()
-    keep = []
-    for i, (G, W, Mom, S) in enumerate(layers):
-        n = W.numel()
-        g = _ptr_array(G, n, "G")
-        keep.append(g)
-        segs[i].n, segs[i].P, segs[i].S = n, len(G), S
-        segs[i].G = ctypes.cast(g, _f32pp)
-        segs[i].W = ctypes.cast(_dev_ptr(W, torch.float32, n, "W"), _f32p)
-        segs[i].Mom = ctypes.cast(_dev_ptr(Mom, torch.float32, n, "Mom"), _f32p)
-    _check(lib().psd_sync_dense_ps_multi(len(layers), segs, lr, mu, wd, _stream_handle(stream)),
-           "psd_sync_dense_ps_multi")
+    DenseMulti(layers).run(lr, mu, stream, wd)
 
 
 class Iteration:

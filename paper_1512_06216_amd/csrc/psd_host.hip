@@ -60,8 +60,8 @@ int32_t psd_version(void) { return 2; }
 psd_status psd_tune_set(int32_t knob, int32_t value)
 {
     if (knob < 0 || knob >= PSD_TUNE_COUNT_) return PSD_E_INVALID;
-    const int32_t limit = knob == PSD_TUNE_SFB_BF16_TILE ? 2 : 2;
-    const int32_t low = knob == PSD_TUNE_SFB_BF16_TILE ? 0 : 1;
+    const int32_t limit = 2;
+    const int32_t low = knob == PSD_TUNE_SFB_F32_TILE ? 1 : 0;
     if (value != -1 && (value < low || value > limit)) return PSD_E_INVALID;
     g_tune[knob].store(value, std::memory_order_relaxed);
     return PSD_OK;
@@ -274,10 +274,22 @@ psd_status fuse_event(hipEvent_t* out)
     return PSD_OK;
 }
 
-bool fusable_ps_layer(const psd_layer_task& t, int32_t rule)
+// may this layer's parameter-server sum share a launch with others that wait for the same event `ready`?
+// may this layer's parameter-server sum share a launch with others that wait for the same event `ready`?
+// Events that order the reconstruction kernels of one iteration one after the other (one per host thread
+// and position, created on first use, never destroyed).
+psd_status chain_event(int i, hipEvent_t* out)
+{
+    static thread_local hipEvent_t ev[2] = {nullptr, nullptr};
+    if (!ev[i & 1]) PSD_HIP_TRY(hipEventCreateWithFlags(&ev[i & 1], hipEventDisableTiming));
+    *out = ev[i & 1];
+    return PSD_OK;
+}
+
+bool fusable_ps_layer(const psd_layer_task& t, int32_t rule, const void* ready)
 {
     const int32_t route = rule == PSD_RULE_ALG3 ? t.plan.route_alg3 : t.plan.route_vs_dense;
-    return route == PSD_ROUTE_PS_DENSE && !t.ev_ready && t.G && t.plan.P <= PSD_MAX_MULTI_WORKERS;
+    return route == PSD_ROUTE_PS_DENSE && t.ev_ready == ready && t.G && t.plan.P <= PSD_MAX_MULTI_WORKERS;
 }
 
 }  // namespace
@@ -293,13 +305,14 @@ psd_status psd_sync_iteration(int32_t L, const psd_layer_task* layers, float lr,
         const int32_t route = rule == PSD_RULE_ALG3 ? t.plan.route_alg3 : t.plan.route_vs_dense;
         hipStream_t st = static_cast<hipStream_t>(t.stream);
 
-        // A run of parameter-server layers whose gradients all exist already (no ev_ready) gains nothing
-        // from being issued one by one: their sums go into ONE launch on the top layer's stream, and the
-        // other layers' streams are ordered after it.
+        // A run of parameter-server layers whose gradients become available together (no ev_ready, or one
+        // and the same event) gains nothing from being issued one by one: their sums go into ONE launch on
+        // the top layer's stream, and the other layers' streams are ordered after it.
         int32_t lo = l;
-        if (fusable_ps_layer(t, rule))
-            while (lo > 0 && l - lo + 1 < PSD_MAX_MULTI_SEGMENTS && fusable_ps_layer(layers[lo - 1], rule)) --lo;
+        if (fusable_ps_layer(t, rule, t.ev_ready))
+            while (lo > 0 && l - lo + 1 < PSD_MAX_MULTI_SEGMENTS && fusable_ps_layer(layers[lo - 1], rule, t.ev_ready)) --lo;
         if (lo < l) {
+            if (t.ev_ready) PSD_HIP_TRY(hipStreamWaitEvent(st, static_cast<hipEvent_t>(t.ev_ready), 0));
             psd_dense_segment segs[PSD_MAX_MULTI_SEGMENTS];
             for (int32_t j = l; j >= lo; --j) {
                 const psd_layer_task& u = layers[j];

@@ -19,6 +19,8 @@ def test_bench_imports_the_oracle_only_inside_the_cpu_baseline_leg():
     assert lines == ["    from oracle import psd_oracle as orc"] * 2      # cpu_baseline and cpu_baseline_configs
     head = src.split("def layer_work", 1)[0]
     assert "from oracle" not in head and "import oracle" not in head
+    extras = open(os.path.join(ROOT, "bench_extras.py")).read()
+    assert "oracle" not in extras
 
 
 def test_product_package_never_imports_the_oracle():
