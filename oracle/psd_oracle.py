@@ -15,6 +15,9 @@ Readings of the paper used here (each is also listed in the design notes):
   * Lambda ("regularisation and momentum", Section 3.3) is applied once per update:
     mom' = mu*mom + lr*(dW + wd*w), w' = w - mom'  (L2 weight decay wd added to the gradient
     before the momentum, as in the Caffe solver the paper builds on; wd = 0 by default).
+  * Bounded staleness (Section 3.2): a worker that reads at clock t is guaranteed the updates of clocks
+    0 .. t-s-1 from all workers; this oracle evaluates exactly that guaranteed view (updates that a real
+    server might deliver early are not included), applied in clock order.
   * Costs: SFB (P-1)^2 B (M+N); full matrices 2 P M N; factors-to-server
     P B (M+N) + P M N (Section 4.3.1).  Alg. 3 compares the first with the third and
     takes SFB on equality.
@@ -23,7 +26,8 @@ Pins (tests/test_oracle_*.py): the three communication volumes and two ratios pr
 Section 4.3.1; finite-difference gradients of a tiny FC layer; K=1 outer product; rank
 bound; linearity; row-permutation invariance; numpy float64 matmul; closed forms of the
 update; torch's CPU bf16 cast; brute-force shard cover; SFB path == PS path; bias gradient
-against finite differences and numpy's column sum.
+against finite differences and numpy's column sum; the staleness window against a literal clock-by-clock
+simulation of a server that withholds each update for s clocks and against the closed form with plain SGD.
 Parity unpinned: none.
 """
 from __future__ import annotations
@@ -274,6 +278,32 @@ def sync_dense_ps(G, W, Mom, lr, mu, S=1, wd=0.0):
     lib().orc_dense_ps(ptrs, P, n, S, W2.ctypes.data_as(f32p), Mom2.ctypes.data_as(f32p),
                        np.float32(lr), np.float32(mu), np.float32(wd))
     return W2, Mom2
+
+
+# --------------------------------------------------------------------------------------
+# Bounded staleness (stale synchronous parallel consistency, Section 3.2)
+# --------------------------------------------------------------------------------------
+def ssp_updates_visible(t, s):
+    """How many clocks' updates a worker that reads the parameters at clock t is guaranteed to see under
+    staleness s: those of clocks 0 .. t-s-1 (Section 3.2), i.e. max(0, t - s).  s = 0 is bulk
+    synchronous: every earlier clock."""
+    t, s = int(t), int(s)
+    if t < 0 or s < 0:
+        raise ValueError("clock and staleness are non-negative")
+    return max(0, t - s)
+
+
+def ssp_visible_state(updates, W0, Mom0, s, t):
+    """Parameters (W, Mom) as guaranteed visible to a reader at clock t under staleness s.
+
+    updates[c] is a function (W, Mom) -> (W', Mom') applying the summed update of clock c (for example
+    lambda W, M: sync_fc_sfb(U_c, V_c, W, M, lr, mu)).  The updates of clocks 0 .. t-s-1 are applied in
+    clock order; later clocks' updates are still pending and not part of the guaranteed view."""
+    W = np.array(W0, dtype=np.float32, copy=True)
+    Mom = np.array(Mom0, dtype=np.float32, copy=True)
+    for c in range(ssp_updates_visible(t, s)):
+        W, Mom = updates[c](W, Mom)
+    return W, Mom
 
 
 def rel_frob(x, ref):
