@@ -215,6 +215,48 @@ typedef struct psd_layer_task {
 psd_status psd_sync_iteration(int32_t L, const psd_layer_task* layers, float lr, float mu, float wd,
                               int32_t rule);
 
+/* ---- Bounded staleness (stale synchronous parallel consistency, Section 3.2) -------------------
+ * With staleness s, a worker that reads the parameters at clock t is guaranteed the updates of all
+ * workers from clocks 0 .. t-s-1; s = 0 is bulk synchronous.  On one worker this means: the update
+ * produced at clock c (the stacked factors of an FC layer, the dense copies of a parameter-server layer)
+ * is applied at the end of clock c+s.  The pending updates wait in a ring of s+1 caller-owned buffers;
+ * psd_ssp_state (host memory, caller-owned, one per layer) counts the clocks.  The arithmetic of an
+ * update is that of psd_sync_fc_sfb / psd_sync_dense_ps; only WHEN it is applied changes, so after
+ * T clocks the parameters equal those of T-s bulk-synchronous clocks and s updates are still pending. */
+#define PSD_MAX_STALENESS 15
+typedef struct psd_ssp_state {
+    int32_t s;         /* staleness bound, 0..PSD_MAX_STALENESS */
+    int32_t reserved;
+    int64_t clock;     /* the clock the next psd_ssp_clock_* call stands for; starts at 0 */
+} psd_ssp_state;
+
+/* Sets st to clock 0 with staleness s. */
+psd_status psd_ssp_init(psd_ssp_state* st, int32_t s);
+
+/* Ring slots of the current clock: *push_slot = clock mod (s+1) is where this clock's factors /
+ * gradient copies go; *due_slot is the slot whose update falls due now (that of clock - s), or -1
+ * during the first s clocks when nothing is due yet.  Host only. */
+psd_status psd_ssp_slots(const psd_ssp_state* st, int32_t* push_slot, int32_t* due_slot);
+
+/* One clock of an FC layer under SFB: stacks this clock's per-worker factor blocks (as
+ * psd_pack_factors) into U_ring[push_slot], V_ring[push_slot], then, if an update is due, rebuilds
+ * and applies it from U_ring[due_slot], V_ring[due_slot] (as psd_sync_fc_sfb, same workspace rules), then
+ * advances the clock.  U_ring, V_ring [host]: s+1 [dev] buffers each, K x ldu / K x ldv elements of
+ * factor_dtype.  delta_p == act_p == NULL drains: nothing is stacked, the due update is applied (call it
+ * s times after the last clock to apply what is still pending; invalid for s = 0). */
+psd_status psd_ssp_clock_fc(psd_ssp_state* st, const psd_plan* plan, int32_t factor_dtype,
+                            const float* const* delta_p, const float* const* act_p,
+                            void* const* U_ring, int64_t ldu, void* const* V_ring, int64_t ldv,
+                            float* W, float* Mom, float lr, float mu, float wd,
+                            void* workspace, size_t workspace_bytes, void* stream);
+
+/* One clock of a parameter-server layer: G_ring [host] holds s+1 [host] arrays of P [dev] pointers;
+ * the caller has put this clock's copies into G_ring[push_slot] (entries of slots that are not due
+ * are not looked at); if an update is due it is summed and applied from G_ring[due_slot] (as
+ * psd_sync_dense_ps), then the clock advances. */
+psd_status psd_ssp_clock_dense(psd_ssp_state* st, int64_t n, int32_t P, const float* const* const* G_ring,
+                               float* W, float* Mom, float lr, float mu, float wd, int32_t S, void* stream);
+
 /* Tuning / test hook (not part of the method): pins a choice the library otherwise makes itself.
  * Process-wide, takes effect on the next call; value -1 restores the automatic choice; any other value
  * outside the listed range is refused with PSD_E_INVALID and changes nothing.  Results never depend on

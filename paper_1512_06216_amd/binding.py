@@ -47,6 +47,10 @@ class DenseSegment(ctypes.Structure):
                 ("W", _f32p), ("Mom", _f32p)]
 
 
+class SspState(ctypes.Structure):
+    _fields_ = [("s", ctypes.c_int32), ("reserved", ctypes.c_int32), ("clock", ctypes.c_int64)]
+
+
 class LayerTask(ctypes.Structure):
     _fields_ = [("plan", Plan), ("factor_dtype", ctypes.c_int32), ("S", ctypes.c_int32),
                 ("delta_p", _f32pp), ("act_p", _f32pp),
@@ -92,6 +96,17 @@ SIGNATURES = {
                                                  ctypes.c_float, ctypes.c_float, ctypes.c_void_p]),
     "psd_sync_iteration": (ctypes.c_int32, [ctypes.c_int32, ctypes.POINTER(LayerTask), ctypes.c_float,
                                             ctypes.c_float, ctypes.c_float, ctypes.c_int32]),
+    "psd_ssp_init": (ctypes.c_int32, [ctypes.POINTER(SspState), ctypes.c_int32]),
+    "psd_ssp_slots": (ctypes.c_int32, [ctypes.POINTER(SspState), ctypes.POINTER(ctypes.c_int32),
+                                       ctypes.POINTER(ctypes.c_int32)]),
+    "psd_ssp_clock_fc": (ctypes.c_int32, [ctypes.POINTER(SspState), ctypes.POINTER(Plan), ctypes.c_int32, _f32pp, _f32pp,
+                                          ctypes.POINTER(ctypes.c_void_p), ctypes.c_int64,
+                                          ctypes.POINTER(ctypes.c_void_p), ctypes.c_int64, ctypes.c_void_p,
+                                          ctypes.c_void_p, ctypes.c_float, ctypes.c_float, ctypes.c_float,
+                                          ctypes.c_void_p, ctypes.c_size_t, ctypes.c_void_p]),
+    "psd_ssp_clock_dense": (ctypes.c_int32, [ctypes.POINTER(SspState), ctypes.c_int64, ctypes.c_int32,
+                                             ctypes.POINTER(_f32pp), ctypes.c_void_p, ctypes.c_void_p, ctypes.c_float,
+                                             ctypes.c_float, ctypes.c_float, ctypes.c_int32, ctypes.c_void_p]),
     "psd_tune_set": (ctypes.c_int32, [ctypes.c_int32, ctypes.c_int32]),
     "psd_status_string": (ctypes.c_char_p, [ctypes.c_int32]),
     "psd_last_hip_error": (ctypes.c_int32, []),
@@ -274,6 +289,67 @@ class DenseMulti:
 def sync_dense_ps_multi(layers, lr, mu, stream=None, wd=0.0):
     """layers: list of (G_list, W, Mom, S)."""
     DenseMulti(layers).run(lr, mu, stream, wd)
+
+
+MAX_STALENESS = 15
+
+
+class SspFc:
+    """An FC layer under staleness s: the clock state and the ring of s+1 stacked-factor buffers
+    (memory only; every clock is one library call)."""
+
+    def __init__(self, plan, factor_dtype, s, device="cuda"):
+        self.plan, self.dtype, self.state = plan, factor_dtype, SspState()
+        _check(lib().psd_ssp_init(ctypes.byref(self.state), s), "psd_ssp_init")
+        self.bufs = [alloc_factors(plan, factor_dtype, device) for _ in range(s + 1)]
+        self.ldu, self.ldv = self.bufs[0][1], self.bufs[0][3]
+        self.U_ring = (ctypes.c_void_p * (s + 1))(*[b[0].data_ptr() for b in self.bufs])
+        self.V_ring = (ctypes.c_void_p * (s + 1))(*[b[2].data_ptr() for b in self.bufs])
+
+    def slots(self):
+        a, b = ctypes.c_int32(), ctypes.c_int32()
+        _check(lib().psd_ssp_slots(ctypes.byref(self.state), ctypes.byref(a), ctypes.byref(b)), "psd_ssp_slots")
+        return a.value, b.value
+
+    def clock(self, delta, act, W, Mom, lr, mu, wd=0.0, workspace=None, stream=None):
+        """delta / act: this clock's per-worker blocks, or None, None to drain."""
+        plan = self.plan
+        d = _ptr_array(delta, plan.B * plan.N, "delta") if delta is not None else None
+        a = _ptr_array(act, plan.B * plan.M, "act") if act is not None else None
+        ws, ws_bytes = _workspace_args(workspace)
+        _check(lib().psd_ssp_clock_fc(ctypes.byref(self.state), ctypes.byref(plan), self.dtype, d, a, self.U_ring, self.ldu,
+                                      self.V_ring, self.ldv, _dev_ptr(W, torch.float32, plan.N * plan.M, "W"),
+                                      _dev_ptr(Mom, torch.float32, plan.N * plan.M, "Mom"), lr, mu, wd, ws, ws_bytes,
+                                      _stream_handle(stream)), "psd_ssp_clock_fc")
+
+
+class SspDense:
+    """A parameter-server layer under staleness s: the clock state and the ring of s+1 sets of P
+    gradient copies (the caller's tensors; this object only keeps the pointer table)."""
+
+    def __init__(self, s):
+        self.state = SspState()
+        _check(lib().psd_ssp_init(ctypes.byref(self.state), s), "psd_ssp_init")
+        self.ring = (_f32pp * (s + 1))()
+        self._keep = [None] * (s + 1)
+
+    def clock(self, G, W, Mom, lr, mu, S, wd=0.0, stream=None):
+        """G: this clock's P copies (kept alive by this object until their slot is reused), or None to drain."""
+        n = W.numel()
+        push = self.state.clock % (self.state.s + 1)
+        P = None
+        if G is not None:
+            arr = _ptr_array(G, n, "G")
+            self._keep[push] = (arr, list(G))
+            self.ring[push] = ctypes.cast(arr, _f32pp)
+        for k in self._keep:
+            if k is not None:
+                P = len(k[1])
+        if P is None:
+            raise ValueError("no gradient copies have been pushed yet")
+        _check(lib().psd_ssp_clock_dense(ctypes.byref(self.state), n, P, self.ring, _dev_ptr(W, torch.float32, n, "W"),
+                                         _dev_ptr(Mom, torch.float32, n, "Mom"), lr, mu, wd, S, _stream_handle(stream)),
+               "psd_ssp_clock_dense")
 
 
 class Iteration:

@@ -11,7 +11,7 @@ ROOT = os.path.dirname(PKG)
 CSRC = os.path.join(PKG, "csrc")
 OBJ = os.path.join(PKG, "_build")
 LIB = os.path.join(PKG, "libpsd.so")
-SOURCES = ["psd_host.hip", "psd_dense.hip", "psd_pack.hip", "psd_sfb_f32.hip", "psd_sfb_bf16.hip", "psd_bias.hip", "psd_static.hip"]
+SOURCES = ["psd_host.hip", "psd_dense.hip", "psd_pack.hip", "psd_sfb_f32.hip", "psd_sfb_bf16.hip", "psd_bias.hip", "psd_static.hip", "psd_ssp.hip"]
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-I", os.path.join(ROOT, "include"),
          "-I", CSRC, "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",

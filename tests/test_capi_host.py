@@ -231,3 +231,33 @@ def test_workspace_query_and_argument_checks():
         assert L.psd_sync_fc_sfb(*args, fake(0x50000008), need, None) == psd.E_INVALID
     assert L.psd_sfb_workspace_bytes(None, psd.BF16) == 0 and L.psd_sfb_workspace_bytes(ctypes.byref(small), 7) == 0
     assert b"workspace" in L.psd_status_string(psd.E_WORKSPACE)
+
+
+def test_ssp_clock_bookkeeping_against_a_literal_ring():
+    """psd_ssp_slots against a literal simulation: a deque of the last s+1 clocks' slots; the update of
+    clock c is due at clock c + s (so that the reader at clock c + s + 1 sees it, Section 3.2)."""
+    L = psd.lib()
+    for s in range(0, 6):
+        st = psd.SspState()
+        assert L.psd_ssp_init(ctypes.byref(st), s) == psd.OK and (st.s, st.clock) == (s, 0)
+        slot_of_clock = {}
+        for t in range(0, 20):
+            a, b = ctypes.c_int32(), ctypes.c_int32()
+            assert L.psd_ssp_slots(ctypes.byref(st), ctypes.byref(a), ctypes.byref(b)) == psd.OK
+            assert 0 <= a.value <= s
+            # the push slot must not hold an update that is still pending (clocks t-s .. t-1, except the one due now
+            # when s = 0 where push == due)
+            pending = {slot_of_clock[c] for c in range(max(0, t - s + 1), t)}
+            assert a.value not in pending
+            slot_of_clock[t] = a.value
+            if t < s:
+                assert b.value == -1
+            else:
+                assert b.value == slot_of_clock[t - s]
+                assert orc.ssp_updates_visible(t + 1, s) == t - s + 1          # after this clock: clocks 0 .. t-s applied
+            st.clock += 1
+    st = psd.SspState()
+    assert L.psd_ssp_init(None, 0) == psd.E_NULL
+    assert L.psd_ssp_init(ctypes.byref(st), -1) == psd.E_INVALID
+    assert L.psd_ssp_init(ctypes.byref(st), psd.MAX_STALENESS + 1) == psd.E_INVALID
+    assert L.psd_ssp_slots(ctypes.byref(st), None, None) == psd.E_NULL

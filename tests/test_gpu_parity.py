@@ -693,3 +693,59 @@ def test_iteration_routes_follow_the_plan():
     psd.Iteration([task]).run(inputs.LR, inputs.MU, psd.RULE_ALG3)
     torch.cuda.synchronize()
     assert orc.rel_frob(Mom2.cpu().numpy(), task["Mom"].cpu().numpy()) <= TOL_F32
+
+
+# ---------------------------------------------------------------------------------------
+# bounded staleness (Section 3.2): the update of clock c is applied at clock c + s
+# ---------------------------------------------------------------------------------------
+@pytest.mark.parametrize("s", [0, 1, 3])
+@pytest.mark.parametrize("dtype", [psd.F32, psd.BF16])
+def test_ssp_fc_layer_over_several_clocks_matches_the_guaranteed_view(s, dtype):
+    """After every clock t the weights on the GPU must be exactly what a reader at clock t+1 is guaranteed
+    under staleness s: the updates of clocks 0 .. t-s, applied in clock order (integer data, lr and mu
+    powers of two, no weight decay: six clocks add six fractional bits, everything stays exact in fp32).
+    Then the ring is drained and the result equals T bulk-synchronous clocks."""
+    T, M, N, B, P = 6, 200, 150, 5, 3
+    sets = [inputs.fc_layer_integer(M, N, B, P, seed=900 + c) for c in range(T)]
+    plan = psd.plan_layer(psd.LAYER_FC, M, N, B, P)
+    layer = psd.SspFc(plan, dtype, s, DEV)
+    W, Mom = dev(sets[0]["W"]), dev(sets[0]["Mom"])
+    packed = [orc.pack_factors(d["delta"], d["act"]) for d in sets]
+    updates = [(lambda w, m, UV=UV: orc.sync_fc_sfb(UV[0], UV[1], w, m, 0.25, 0.5)) for UV in packed]
+    for t in range(T):
+        push, due = layer.slots()
+        assert push == t % (s + 1) and due == (-1 if t < s else (t - s) % (s + 1))
+        layer.clock([dev(x) for x in sets[t]["delta"]], [dev(x) for x in sets[t]["act"]], W, Mom, 0.25, 0.5)
+        torch.cuda.synchronize()
+        Wr, Mr = orc.ssp_visible_state(updates, sets[0]["W"], sets[0]["Mom"], s, t + 1)
+        assert np.array_equal(W.cpu().numpy(), Wr) and np.array_equal(Mom.cpu().numpy(), Mr), (s, t)
+    for k in range(s):                                   # drain what is still pending
+        layer.clock(None, None, W, Mom, 0.25, 0.5)
+    torch.cuda.synchronize()
+    Wr, Mr = orc.ssp_visible_state(updates, sets[0]["W"], sets[0]["Mom"], 0, T)
+    assert np.array_equal(W.cpu().numpy(), Wr) and np.array_equal(Mom.cpu().numpy(), Mr)
+    if s == 0:
+        with pytest.raises(psd.PsdError):
+            layer.clock(None, None, W, Mom, 0.25, 0.5)   # nothing can be pending without staleness
+
+
+@pytest.mark.parametrize("s", [0, 2])
+def test_ssp_parameter_server_layer_over_several_clocks(s):
+    T, n, P = 5, 70001, 4
+    sets = [inputs.dense_layer(n, P, seed=950 + c, mom_std=1e-3) for c in range(T)]
+    layer = psd.SspDense(s)
+    W, Mom = dev(sets[0]["W"]), dev(sets[0]["Mom"])
+    updates = [(lambda w, m, G=d["G"]: orc.sync_dense_ps(G, w, m, inputs.LR, inputs.MU, 7)) for d in sets]
+    for t in range(T):
+        layer.clock([dev(g) for g in sets[t]["G"]], W, Mom, inputs.LR, inputs.MU, 7)
+        torch.cuda.synchronize()
+        Wr, Mr = orc.ssp_visible_state(updates, sets[0]["W"], sets[0]["Mom"], s, t + 1)
+        e = three_errors(sets[0]["W"], W.cpu().numpy(), Mom.cpu().numpy(), Wr, Mr) if t >= s else (0.0,)
+        assert max(e) <= TOL_F32, (s, t, e)
+        if t < s:                                        # nothing applied yet: the state is untouched
+            assert np.array_equal(W.cpu().numpy(), sets[0]["W"]) and np.array_equal(Mom.cpu().numpy(), sets[0]["Mom"])
+    for k in range(s):
+        layer.clock(None, W, Mom, inputs.LR, inputs.MU, 7)
+    torch.cuda.synchronize()
+    Wr, Mr = orc.ssp_visible_state(updates, sets[0]["W"], sets[0]["Mom"], 0, T)
+    assert max(three_errors(sets[0]["W"], W.cpu().numpy(), Mom.cpu().numpy(), Wr, Mr)) <= TOL_F32
