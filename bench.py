@@ -40,7 +40,7 @@ PREWARM_MS = 150.0      # untimed work before the W warm-up steps: the clocks of
 # HBM bytes per launch of the dominant kernel measured with rocprofv3 --pmc (FETCH_SIZE and
 # WRITE_SIZE runs, scaled by a copy kernel of known size); filled in from the committed
 # profile summaries, None where not measured.
-MEASURED_TRAFFIC_BYTES = {"bf16": 922_900_000, "f32": None}   # fc6 launch; profiles/bench_config5_bf16_hbm_traffic.txt
+MEASURED_TRAFFIC_BYTES = {"bf16": 931_700_000, "f32": None}   # fc6 launch; profiles/bench_config5_bf16_hbm_traffic.txt
 
 
 class HipEvents:
@@ -293,21 +293,21 @@ def durations(ev, marks, n_layers):
     return dur
 
 
-def roofline_of(leg, dur, layers, name):
+def roofline_of(leg, dur, layers, name, alone=True):
     """Roofline object of the dominant kernel: the reconstruct+update kernel of fc6 (it has a kernel
     instantiation of its own, so a per-kernel profile reports exactly these launches)."""
     j = [i for i, L in enumerate(layers) if L["name"] == "fc6"][0]
     w = leg.work[j]
     avg_ms = float(dur[:, j].mean())
     med_ms = float(np.median(dur[:, j]))
-    alone_ms = leg.layer_alone_ms(j)
+    alone_ms = leg.layer_alone_ms(j) if alone else avg_ms
     peak_tf = PEAK_MFMA_TFLOPS[name]
 
     def fr(ms):
         return dict(avg_launch_ms=round(ms, 5), hbm_gbps=round(w["bytes"] / ms / 1e6, 1),
                     hbm_frac=round(w["bytes"] / ms / 1e6 / PEAK_HBM_GBS, 4), mfma_tflops=round(w["flops"] / ms / 1e9, 2),
                     mfma_frac=round(w["flops"] / ms / 1e9 / peak_tf, 4))
-    inside, alone = fr(avg_ms), fr(alone_ms)
+    inside, alone_fr = fr(avg_ms), (fr(alone_ms) if alone else None)
     if name == "bf16":
         # bf16 factors: 16 B of W/Mom traffic per 2K flops puts the kernel on the HBM side of the ridge
         r = dict(bound="hbm", achieved=inside["hbm_gbps"], peak=PEAK_HBM_GBS, unit="GB/s", frac=inside["hbm_frac"],
@@ -319,7 +319,7 @@ def roofline_of(leg, dur, layers, name):
              algorithmic_bytes_per_launch=int(w["bytes"]), flops_per_launch=int(w["flops"]),
              note="achieved / frac: mean launch duration inside the timed iterations (other layers' kernels run "
                   "beside it on their own streams); 'alone': the same launch back to back with an idle GPU",
-             in_iteration=dict(inside, median_launch_ms=round(med_ms, 5)), alone=alone)
+             in_iteration=dict(inside, median_launch_ms=round(med_ms, 5)), alone=alone_fr)
     return r
 
 
@@ -337,6 +337,9 @@ def main():
     ap.add_argument("--no-side-legs", action="store_true",
                     help="skip the legs reported beside the headline (overlapping steps, one stream, the other factor dtype, "
                          "dense sweep)")
+    ap.add_argument("--no-alone", action="store_true",
+                    help="skip the back-to-back launches of single kernels (so that a kernel trace of the run holds "
+                         "nothing but whole iterations)")
     ap.add_argument("--extras", default=None, help="also time configs 1-4 and more; write JSON here")
     ap.add_argument("--copy-probe", type=int, default=0, metavar="MiB",
                     help="only run a plain device-to-device copy of this many MiB, 10 times (calibrates the "
@@ -392,12 +395,12 @@ def main():
         per_layer[L["name"]] = dict(median_ms=round(med, 5), mean_ms=round(float(dur[:, j].mean()), 5),
                                     min_ms=round(float(dur[:, j].min()), 5), GBps=round(w["bytes"] / med / 1e6, 1),
                                     TFLOPs=round(w["flops"] / med / 1e9, 2))
-    roofline = roofline_of(leg, dur, layers, args.fc_dtype)
+    roofline = roofline_of(leg, dur, layers, args.fc_dtype, alone=not args.no_alone)
 
     # the five conv layers are one launch: every conv layer's event pair brackets that launch
     conv_bytes = sum(work[j]["bytes"] for j in conv_idx)
     conv_ms = float(np.median(dur[:, conv_idx[0]]))
-    conv_alone = leg.conv_alone_ms()
+    conv_alone = leg.conv_alone_ms() if not args.no_alone else conv_ms
     dense = {"launch": "the five conv layers in one psd_sync_dense_ps_multi launch (2.3M keys, P = 8, S = 8)",
              "bytes_per_step": conv_bytes,
              "in_iteration": {"median_ms": round(conv_ms, 5), "GBps": round(conv_bytes / conv_ms / 1e6, 1),

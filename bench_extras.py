@@ -1,9 +1,21 @@
 """Optional per-configuration timings for bench.py --extras: the four single-layer FC
-configurations (pack and reconstruct+update timed separately) and a size sweep of the
-dense parameter-server kernel.  Timing only: no arithmetic of the method lives here."""
+configurations (pack and reconstruct+update timed separately), the second-workload and VGG-16-sized
+shapes, a sweep of the contraction length on the fc6 shape, a size sweep of the dense parameter-server
+kernel and the wait-free issue measurement.  Timing only: no arithmetic of the method lives here.
+
+Run alone it launches ONE kernel family back to back, for rocprofv3 (kernel stats or counters of exactly
+that kernel):
+    python3 bench_extras.py --layer fc6 --dtype bf16 [--iters 40]      # reconstruct + update only
+    python3 bench_extras.py --dense 37748736 [--iters 40]              # parameter-server sum + update only
+"""
 from __future__ import annotations
 
+import os
+import sys
+
 import numpy as np
+
+sys.path.insert(0, os.path.dirname(os.path.abspath(__file__)))
 
 PEAK_HBM_GBS = 8000.0
 PEAK_TF = {"bf16": 2500.0, "f32": 157.3}
@@ -33,11 +45,24 @@ def _time_ms(torch, fn, n_sets, iters=20, warmup_ms=100.0, batches=5):
     return float(np.median(ts))
 
 
-def fc_config(psd, inputs, torch, dev, cfg_id, dtype_name=None, working_set_mb=600):
-    c = inputs.FC_CONFIGS[cfg_id]
-    dtype_name = dtype_name or c["factor_dtype"]
+# FC shapes beyond the four configurations: the ImageNet-22K network's FC stack (Section 5.1.3), GoogLeNet's
+# single FC layer at batch 32 per node (Section 5.1.2) and a VGG-16-sized FC stack (Table 3) at batch 256 per node
+EXTRA_SHAPES = {"in22k_fc": (3000, 3000, 256, 8), "in22k_cls": (3000, 21841, 256, 8), "googlenet_fc": (1024, 1000, 32, 8),
+                "vgg_fc6": (25088, 4096, 256, 8), "vgg_fc7": (4096, 4096, 256, 8), "vgg_fc8": (4096, 1000, 256, 8)}
+NAMED_LAYERS = {"cfg1": 1, "cfg2": 2, "fc8": 2, "fc6": 3, "cfg3": 3, "cls22k": 4, "cfg4": 4}
+
+
+def fc_config(psd, inputs, torch, dev, cfg_id, dtype_name=None, working_set_mb=600, shape=None, only_sfb_iters=0):
+    """cfg_id 1..4, or shape=(name, M, N, B, P) for any other layer."""
+    if shape is None:
+        c = inputs.FC_CONFIGS[cfg_id]
+        dtype_name = dtype_name or c["factor_dtype"]
+        d = inputs.fc_config(cfg_id)
+    else:
+        c = dict(name=shape[0])
+        d = inputs.fc_layer(shape[1], shape[2], shape[3], shape[4], seed=sum(shape[1:]),
+                            delta_kind="softmax" if shape[2] == 21841 else "gauss")
     dtype = psd.BF16 if dtype_name == "bf16" else psd.F32
-    d = inputs.fc_config(cfg_id)
     M, N, B, P = d["M"], d["N"], d["B"], d["P"]
     K = P * B
     es = 2 if dtype_name == "bf16" else 4
@@ -74,6 +99,12 @@ def fc_config(psd, inputs, torch, dev, cfg_id, dtype_name=None, working_set_mb=6
 
     for i in range(n_sets):
         pack(i)
+    if only_sfb_iters:                       # profiling mode: nothing but this kernel, back to back
+        torch.cuda.synchronize()
+        for i in range(only_sfb_iters):
+            sfb(i % n_sets)
+        torch.cuda.synchronize()
+        return None
     t_pack = _time_ms(torch, pack, n_sets)
     t_sfb = _time_ms(torch, sfb, n_sets)
     t_both = _time_ms(torch, both, n_sets)
@@ -89,6 +120,41 @@ def fc_config(psd, inputs, torch, dev, cfg_id, dtype_name=None, working_set_mb=6
                 pack_ms=round(t_pack, 5), pack_GBps=round(bytes_pack / t_pack / 1e6, 1),
                 pack_plus_sfb_ms=round(t_both, 5), pack_plus_sfb_TFLOPs=round(flops / t_both / 1e9, 2),
                 bias_ms=round(t_bias, 5), bias_GBps=round((K * N * es + 16 * N) / t_bias / 1e6, 1))
+
+
+def sfb_k_sweep(psd, inputs, torch, dev, M=9216, N=4096, P=8, batches=(4, 64, 128, 256, 512), dtype_name="bf16"):
+    """Reconstruct + update on the fc6 shape at different contraction lengths K = P*B: the time is close
+    to a + b*K; a is what the update of W and Mom costs (K = 32 is nothing else), b*K the k loop."""
+    dtype = psd.BF16 if dtype_name == "bf16" else psd.F32
+    td = torch.bfloat16 if dtype_name == "bf16" else torch.float32
+    W = [torch.randn(N, M, device=dev) * 1e-2 for _ in range(2)]
+    Mom = [torch.zeros(N, M, device=dev) for _ in range(2)]
+    out = []
+    for B in batches:
+        K = P * B
+        plan = psd.plan_layer(psd.LAYER_FC, M, N, B, P)
+        ldu, ldv = psd.factor_ld(N, dtype), psd.factor_ld(M, dtype)
+        U = [(torch.randn(K, ldu, device=dev) * 1e-3).to(td) for _ in range(2)]
+        V = [torch.relu(torch.randn(K, ldv, device=dev)).to(td) for _ in range(2)]
+
+        def run(i):
+            psd.sync_fc_sfb(plan, dtype, U[i], ldu, V[i], ldv, W[i], Mom[i], inputs.LR, inputs.MU)
+        t = _time_ms(torch, run, 2)
+        out.append(dict(K=K, ms=round(t, 5), TFLOPs=round(2.0 * N * M * K / t / 1e9, 1),
+                        GBps=round((16.0 * N * M + K * (M + N) * (2 if dtype_name == "bf16" else 4)) / t / 1e6, 1)))
+    a = np.polyfit([o["K"] for o in out], [o["ms"] for o in out], 1)
+    return dict(shape="%d -> %d" % (M, N), factor_dtype=dtype_name, points=out,
+                fit_us_per_1024_k=round(float(a[0]) * 1024 * 1e3, 2), fit_intercept_us=round(float(a[1]) * 1e3, 2))
+
+
+def dense_only(psd, inputs, torch, dev, n, iters, P=8, S=8):
+    sets = [([torch.randn(n, device=dev) * 1e-3 for _ in range(P)], torch.randn(n, device=dev) * 1e-2,
+             torch.zeros(n, device=dev)) for _ in range(2)]
+    torch.cuda.synchronize()
+    for i in range(iters):
+        G, W, Mom = sets[i % 2]
+        psd.sync_dense_ps(G, W, Mom, inputs.LR, inputs.MU, S)
+    torch.cuda.synchronize()
 
 
 def dense_sweep(psd, inputs, torch, dev, sizes=(2332704, 16777216, 37748736, 89460736), P=8, S=8):
@@ -200,6 +266,43 @@ def run(psd, inputs, torch, dev):
     for cfg, dt in [(1, "f32"), (2, "f32"), (2, "bf16"), (3, "bf16"), (3, "f32"), (4, "bf16")]:
         res["fc"].append(fc_config(psd, inputs, torch, dev, cfg, dt))
         torch.cuda.empty_cache()
+    res["fc_other_shapes"] = []
+    for name, (M, N, B, P) in EXTRA_SHAPES.items():
+        for dt in ("bf16", "f32"):
+            res["fc_other_shapes"].append(fc_config(psd, inputs, torch, dev, None, dt, shape=(name, M, N, B, P)))
+            torch.cuda.empty_cache()
+    res["fc6_k_sweep"] = [sfb_k_sweep(psd, inputs, torch, dev, dtype_name="bf16"),
+                          sfb_k_sweep(psd, inputs, torch, dev, dtype_name="f32", batches=(4, 64, 128, 256))]
+    torch.cuda.empty_cache()
     res["dense_sweep"] = dense_sweep(psd, inputs, torch, dev)
     res["dwbp_overlap"] = dwbp_overlap(psd, inputs, torch, dev)
     return res
+
+
+def main():
+    import argparse
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--layer", default=None, help="cfg1..cfg4, fc6, fc8, cls22k or one of %s" % ", ".join(EXTRA_SHAPES))
+    ap.add_argument("--dtype", choices=["bf16", "f32"], default="bf16")
+    ap.add_argument("--dense", type=int, default=0, metavar="KEYS")
+    ap.add_argument("--iters", type=int, default=40)
+    args = ap.parse_args()
+    import torch
+    from paper_1512_06216_amd import binding as psd
+    from paper_1512_06216_amd import inputs
+    psd.lib()
+    dev = "cuda:0"
+    if args.dense:
+        dense_only(psd, inputs, torch, dev, args.dense, args.iters)
+    elif args.layer in NAMED_LAYERS:
+        fc_config(psd, inputs, torch, dev, NAMED_LAYERS[args.layer], args.dtype, only_sfb_iters=args.iters)
+    elif args.layer in EXTRA_SHAPES:
+        fc_config(psd, inputs, torch, dev, None, args.dtype, shape=(args.layer,) + EXTRA_SHAPES[args.layer],
+                  only_sfb_iters=args.iters)
+    else:
+        ap.error("give --layer or --dense")
+    print("done")
+
+
+if __name__ == "__main__":
+    main()
