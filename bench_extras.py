@@ -7,6 +7,10 @@ Run alone it launches ONE kernel family back to back, for rocprofv3 (kernel stat
 that kernel):
     python3 bench_extras.py --layer fc6 --dtype bf16 [--iters 40]      # reconstruct + update only
     python3 bench_extras.py --dense 37748736 [--iters 40]              # parameter-server sum + update only
+and two studies of how the MFMA loop and the W / Mom traffic share the chip (text on stdout):
+    python3 bench_extras.py --study skew         # odd XCDs start late: does putting the phases out of step pay?
+    python3 bench_extras.py --study partition    # reconstruction and a dense stream on disjoint sets of CUs
+    python3 bench_extras.py --study ksweep       # time over the contraction length on the fc6 and fc8 shapes
 """
 from __future__ import annotations
 
@@ -127,24 +131,123 @@ def sfb_k_sweep(psd, inputs, torch, dev, M=9216, N=4096, P=8, batches=(4, 64, 12
     to a + b*K; a is what the update of W and Mom costs (K = 32 is nothing else), b*K the k loop."""
     dtype = psd.BF16 if dtype_name == "bf16" else psd.F32
     td = torch.bfloat16 if dtype_name == "bf16" else torch.float32
-    W = [torch.randn(N, M, device=dev) * 1e-2 for _ in range(2)]
-    Mom = [torch.zeros(N, M, device=dev) for _ in range(2)]
+    n_sets = int(min(16, max(2, np.ceil(600e6 / (8.0 * N * M)))))      # W and Mom rotate over > 600 MB: past the last-level cache
+    W = [torch.randn(N, M, device=dev) * 1e-2 for _ in range(n_sets)]
+    Mom = [torch.zeros(N, M, device=dev) for _ in range(n_sets)]
     out = []
     for B in batches:
         K = P * B
         plan = psd.plan_layer(psd.LAYER_FC, M, N, B, P)
         ldu, ldv = psd.factor_ld(N, dtype), psd.factor_ld(M, dtype)
-        U = [(torch.randn(K, ldu, device=dev) * 1e-3).to(td) for _ in range(2)]
-        V = [torch.relu(torch.randn(K, ldv, device=dev)).to(td) for _ in range(2)]
+        U = [(torch.randn(K, ldu, device=dev) * 1e-3).to(td) for _ in range(n_sets)]
+        V = [torch.relu(torch.randn(K, ldv, device=dev)).to(td) for _ in range(n_sets)]
 
         def run(i):
             psd.sync_fc_sfb(plan, dtype, U[i], ldu, V[i], ldv, W[i], Mom[i], inputs.LR, inputs.MU)
-        t = _time_ms(torch, run, 2)
+        t = _time_ms(torch, run, n_sets)
         out.append(dict(K=K, ms=round(t, 5), TFLOPs=round(2.0 * N * M * K / t / 1e9, 1),
                         GBps=round((16.0 * N * M + K * (M + N) * (2 if dtype_name == "bf16" else 4)) / t / 1e6, 1)))
     a = np.polyfit([o["K"] for o in out], [o["ms"] for o in out], 1)
     return dict(shape="%d -> %d" % (M, N), factor_dtype=dtype_name, points=out,
                 fit_us_per_1024_k=round(float(a[0]) * 1024 * 1e3, 2), fit_intercept_us=round(float(a[1]) * 1e3, 2))
+
+
+def _bf16_layer(psd, torch, dev, M, N, B, P=8, n_sets=2):
+    plan = psd.plan_layer(psd.LAYER_FC, M, N, B, P)
+    K = B * P
+    ldu, ldv = psd.factor_ld(N, psd.BF16), psd.factor_ld(M, psd.BF16)
+    sets = []
+    for _ in range(n_sets):
+        U = (torch.randn(K, ldu, device=dev) * 1e-3).to(torch.bfloat16)
+        V = torch.relu(torch.randn(K, ldv, device=dev)).to(torch.bfloat16)
+        sets.append((U, V, torch.randn(N, M, device=dev) * 1e-2, torch.zeros(N, M, device=dev)))
+
+    def run(i, stream=None):
+        U, V, W, Mom = sets[i % n_sets]
+        psd.sync_fc_sfb(plan, psd.BF16, U, ldu, V, ldv, W, Mom, 0.01, 0.9, stream=stream)
+    return run
+
+
+def phase_skew_study(psd, torch, dev, skews=(0, 10, 20, 30, 40, 60)):
+    """bf16 reconstruct + update with the first workgroups of the odd XCDs started `skew` microseconds late
+    (PSD_TUNE_SFB_BF16_SKEW_US).  If an XCD's MFMA loop ran faster while the other half of the chip is in its
+    update phase, or its update faster while the other half computes, a skew of about half a round would pay
+    back more than it costs, the more so the more rounds a launch has (fc6: 3, the 22K layer: 9)."""
+    print("# time per launch (us, median of 5 x 20) over the start delay of the odd XCDs")
+    for name, (M, N) in (("fc6 9216 -> 4096", (9216, 4096)), ("22K classifier 4096 -> 21841", (4096, 21841))):
+        run = _bf16_layer(psd, torch, dev, M, N, 256)
+        row = []
+        for us in skews:
+            psd.tune_set(psd.TUNE_SFB_BF16_SKEW_US, us)
+            row.append("%d us: %.1f" % (us, _time_ms(torch, run, 2) * 1e3))
+        psd.tune_set(psd.TUNE_SFB_BF16_SKEW_US, -1)
+        print("%-30s %s" % (name, "   ".join(row)), flush=True)
+        del run
+        torch.cuda.empty_cache()
+
+
+def cu_partition_study(psd, torch, dev, n=37748736, P=8):
+    """A reconstruction that is nearly all MFMA loop (4096 -> 4096 at K = 16384) and the dense parameter-server
+    stream, each alone on a subset of the CUs (streams created with a CU mask), then both at once on disjoint
+    subsets, next to the two run one after the other on the whole chip."""
+    import ctypes
+    hip = ctypes.CDLL("libamdhip64.so")
+    hip.hipExtStreamCreateWithCUMask.argtypes = [ctypes.POINTER(ctypes.c_void_p), ctypes.c_uint32,
+                                                 ctypes.POINTER(ctypes.c_uint32)]
+
+    def masked_stream(lo, hi):
+        bits = (ctypes.c_uint32 * 8)()
+        for b in range(lo, hi):
+            bits[b // 32] |= 1 << (b % 32)
+        st = ctypes.c_void_p()
+        if hip.hipExtStreamCreateWithCUMask(ctypes.byref(st), 8, bits) != 0:
+            raise RuntimeError("hipExtStreamCreateWithCUMask failed")
+        return st.value
+
+    sfb = _bf16_layer(psd, torch, dev, 4096, 4096, 2048)
+    G = [torch.randn(n, device=dev) * 1e-3 for _ in range(P)]
+    dW, dMom = torch.randn(n, device=dev) * 1e-2, torch.zeros(n, device=dev)
+
+    def dense(i, stream=None):
+        psd.sync_dense_ps(G, dW, dMom, 0.01, 0.9, 8, stream=stream)
+
+    def timed(fa, sa, fb, sb, reps=9):
+        res = []
+        for r in range(reps + 3):
+            torch.cuda.synchronize()
+            ev = [torch.cuda.Event(enable_timing=True) for _ in range(4)]
+            if fa:
+                xa = torch.cuda.ExternalStream(sa)
+                ev[0].record(xa); fa(r, sa); fa(r + 1, sa); ev[1].record(xa)
+            if fb:
+                xb = torch.cuda.ExternalStream(sb)
+                ev[2].record(xb); fb(r, sb); fb(r + 1, sb); ev[3].record(xb)
+            torch.cuda.synchronize()
+            res.append((ev[0].elapsed_time(ev[1]) * 1e3 if fa else 0.0, ev[2].elapsed_time(ev[3]) * 1e3 if fb else 0.0))
+        return np.median(np.array(res[3:]), axis=0)
+
+    _time_ms(torch, lambda i: sfb(i), 2, iters=4, batches=1)          # settle the clocks
+    print("# A = two launches of the bf16 reconstruction 4096 -> 4096, K = 16384;  B = two launches of the dense sum + update,")
+    print("# %d keys, P = %d;  microseconds, medians of 9" % (n, P))
+    for a in (256, 192, 128, 224):
+        sa = masked_stream(0, a)
+        sb = masked_stream(a, 256) if a < 256 else masked_stream(0, 256)
+        ta = timed(sfb, sa, None, None)[0]
+        tb = timed(None, None, dense, sb)[1]
+        both = timed(sfb, sa, dense, sb)
+        tag = "disjoint" if a < 256 else "the same"
+        print("A on %3d CUs alone %7.1f | B on %3d CUs alone %7.1f | at once on %s CUs: A %7.1f  B %7.1f" %
+              (a, ta, 256 - a if a < 256 else 256, tb, tag, both[0], both[1]), flush=True)
+
+
+def k_sweep_study(psd, inputs, torch, dev):
+    for M, N in ((9216, 4096), (4096, 1000)):
+        for dt, batches in (("bf16", (4, 64, 128, 256, 512)), ("f32", (4, 64, 128, 256))):
+            r = sfb_k_sweep(psd, inputs, torch, dev, M=M, N=N, batches=batches, dtype_name=dt)
+            print("%s %s: %s | fit %.1f us + %.1f us per 1024 k" % (
+                r["shape"], dt, "  ".join("K=%d: %.1f us" % (p["K"], p["ms"] * 1e3) for p in r["points"]),
+                r["fit_intercept_us"], r["fit_us_per_1024_k"]), flush=True)
+            torch.cuda.empty_cache()
 
 
 def dense_only(psd, inputs, torch, dev, n, iters, P=8, S=8):
@@ -286,13 +389,20 @@ def main():
     ap.add_argument("--dtype", choices=["bf16", "f32"], default="bf16")
     ap.add_argument("--dense", type=int, default=0, metavar="KEYS")
     ap.add_argument("--iters", type=int, default=40)
+    ap.add_argument("--study", choices=["skew", "partition", "ksweep"], default=None)
     args = ap.parse_args()
     import torch
     from paper_1512_06216_amd import binding as psd
     from paper_1512_06216_amd import inputs
     psd.lib()
     dev = "cuda:0"
-    if args.dense:
+    if args.study == "skew":
+        phase_skew_study(psd, torch, dev)
+    elif args.study == "partition":
+        cu_partition_study(psd, torch, dev)
+    elif args.study == "ksweep":
+        k_sweep_study(psd, inputs, torch, dev)
+    elif args.dense:
         dense_only(psd, inputs, torch, dev, args.dense, args.iters)
     elif args.layer in NAMED_LAYERS:
         fc_config(psd, inputs, torch, dev, NAMED_LAYERS[args.layer], args.dtype, only_sfb_iters=args.iters)

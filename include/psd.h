@@ -263,8 +263,13 @@ psd_status psd_ssp_clock_dense(psd_ssp_state* st, int64_t n, int32_t P, const fl
  * these choices (only speed does).
  *   PSD_TUNE_SFB_BF16_TILE: workgroup tile of the bf16 reconstruction, rows n x columns m of W:
  *                           0 = 128 x 256, 1 = 128 x 192, 2 = 128 x 128
- *   PSD_TUNE_SFB_F32_TILE:  ... of the fp32 reconstruction: 1 = 64 x 128, 2 = 128 x 128 */
-enum { PSD_TUNE_SFB_BF16_TILE = 0, PSD_TUNE_SFB_F32_TILE = 1, PSD_TUNE_COUNT_ = 2 };
+ *   PSD_TUNE_SFB_F32_TILE:  ... of the fp32 reconstruction: 1 = 64 x 128, 2 = 128 x 128
+ *   PSD_TUNE_SFB_BF16_SKEW_US: 0..200 (default and -1: 0).  The workgroups of the bf16 reconstruction that
+ *                           start first on the odd-numbered accelerator dies (XCDs) wait this many
+ *                           microseconds before they begin, so that one half of the chip is in its MFMA
+ *                           loop while the other half streams its W / Mom update.  A measurement aid
+ *                           for studying how the two phases share the chip. */
+enum { PSD_TUNE_SFB_BF16_TILE = 0, PSD_TUNE_SFB_F32_TILE = 1, PSD_TUNE_SFB_BF16_SKEW_US = 2, PSD_TUNE_COUNT_ = 3 };
 psd_status psd_tune_set(int32_t knob, int32_t value);
 
 const char* psd_status_string(psd_status s);

@@ -19,7 +19,7 @@ LAYER_CONV, LAYER_FC = 0, 1
 ROUTE_PS_DENSE, ROUTE_SFB, ROUTE_SF_PS = 0, 1, 2
 RULE_ALG3, RULE_SFB_VS_DENSE = 0, 1
 F32, BF16 = 0, 1
-TUNE_SFB_BF16_TILE, TUNE_SFB_F32_TILE = 0, 1
+TUNE_SFB_BF16_TILE, TUNE_SFB_F32_TILE, TUNE_SFB_BF16_SKEW_US = 0, 1, 2
 ROUTE_NAMES = {ROUTE_PS_DENSE: "PS_DENSE", ROUTE_SFB: "SFB", ROUTE_SF_PS: "SF_PS"}
 MAX_WORKERS, MAX_MULTI_SEGMENTS, MAX_MULTI_WORKERS = 64, 16, 16
 STATIC_SCRATCH_BYTES = 16 << 20

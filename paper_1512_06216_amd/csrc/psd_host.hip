@@ -11,7 +11,7 @@ psd_status hip_failed(hipError_t e)
     return PSD_E_HIP;
 }
 
-static std::atomic<int> g_tune[PSD_TUNE_COUNT_] = {{-1}, {-1}};
+static std::atomic<int> g_tune[PSD_TUNE_COUNT_] = {{-1}, {-1}, {-1}};
 int tune_value(int knob) { return knob >= 0 && knob < PSD_TUNE_COUNT_ ? g_tune[knob].load(std::memory_order_relaxed) : -1; }
 
 int device_cu_count()
@@ -60,7 +60,7 @@ int32_t psd_version(void) { return 2; }
 psd_status psd_tune_set(int32_t knob, int32_t value)
 {
     if (knob < 0 || knob >= PSD_TUNE_COUNT_) return PSD_E_INVALID;
-    const int32_t limit = 2;
+    const int32_t limit = knob == PSD_TUNE_SFB_BF16_SKEW_US ? 200 : 2;
     const int32_t low = knob == PSD_TUNE_SFB_F32_TILE ? 1 : 0;
     if (value != -1 && (value < low || value > limit)) return PSD_E_INVALID;
     g_tune[knob].store(value, std::memory_order_relaxed);

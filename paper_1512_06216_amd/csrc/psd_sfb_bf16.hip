@@ -69,8 +69,16 @@ __global__ void __launch_bounds__(C::THREADS, C::OCC)
 sfb_bf16_kernel(const uint16_t* __restrict__ U, int64_t ldu, const uint16_t* __restrict__ V, int64_t ldv,
                 float* __restrict__ W, float* __restrict__ Mom, int N, int M, int K, float lr, float mu, float wd,
                 int tiles_n, int tiles_m, uint32_t u_bytes, uint32_t v_bytes, float* __restrict__ part,
-                int64_t part_stride, int stages_per_split)
+                int64_t part_stride, int stages_per_split, int skew_blocks, int skew_ticks)
 {
+    // Measurement aid (off unless asked for): the workgroups that start first on the odd-numbered
+    // XCDs wait skew_ticks of the 100 MHz wall clock, which puts the two halves of the chip out of
+    // phase (MFMA loop on one, W / Mom update on the other).  The wait ends by the clock; the
+    // iteration cap only bounds it should the clock not advance.
+    if (skew_ticks > 0 && (blockIdx.x & 1) && static_cast<int>(blockIdx.x) < skew_blocks) {
+        const long long t0 = wall_clock64();
+        for (int i = 0; i < 200000 && wall_clock64() - t0 < skew_ticks; ++i) __builtin_amdgcn_s_sleep(8);
+    }
     extern __shared__ __attribute__((aligned(1024))) uint16_t lds[];
     const uint32_t lds0 = static_cast<uint32_t>(reinterpret_cast<uintptr_t>(
         (__attribute__((address_space(3))) void*)lds));
@@ -335,12 +343,14 @@ psd_status launch_cfg(const uint16_t* U, int64_t ldu, const uint16_t* V, int64_t
                                         hipFuncAttributeMaxDynamicSharedMemorySize, int(C::LDS_BYTES)));
         attr_done.store(true, std::memory_order_release);
     }
+    const int skew = tune_value(PSD_TUNE_SFB_BF16_SKEW_US);
     const int64_t stages = (K + KT - 1) / KT;
     const int sps = static_cast<int>((stages + splits - 1) / splits);
     hipLaunchKernelGGL(kern, dim3(static_cast<uint32_t>(tiles * splits)), dim3(C::THREADS), C::LDS_BYTES, st, U, ldu, V,
                        ldv, W, Mom, static_cast<int>(N), static_cast<int>(M), static_cast<int>(K), lr, mu, wd,
                        static_cast<int>(tiles_n), static_cast<int>(tiles_m), static_cast<uint32_t>(u_bytes),
-                       static_cast<uint32_t>(v_bytes), part, sfb_part_stride(N, M), sps);
+                       static_cast<uint32_t>(v_bytes), part, sfb_part_stride(N, M), sps,
+                       device_cu_count() * C::OCC, skew > 0 ? skew * 100 : 0);
     PSD_HIP_TRY(hipGetLastError());
     if (splits > 1) return launch_sfb_reduce(part, splits, N, M, W, Mom, lr, mu, wd, st);
     return PSD_OK;

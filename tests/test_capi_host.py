@@ -183,12 +183,13 @@ def test_binding_fails_loudly_without_the_library(monkeypatch):
 
 def test_tune_hook_accepts_listed_values_only():
     L = psd.lib()
-    for knob, good, bad in ((psd.TUNE_SFB_BF16_TILE, (0, 1, 2, -1), (3, -2, 100)), (psd.TUNE_SFB_F32_TILE, (1, 2, -1), (0, 3))):
+    for knob, good, bad in ((psd.TUNE_SFB_BF16_TILE, (0, 1, 2, -1), (3, -2, 100)), (psd.TUNE_SFB_F32_TILE, (1, 2, -1), (0, 3)),
+                            (psd.TUNE_SFB_BF16_SKEW_US, (0, 20, 200, -1), (201, -2))):
         for v in good:
             assert L.psd_tune_set(knob, v) == psd.OK
         for v in bad:
             assert L.psd_tune_set(knob, v) == psd.E_INVALID
-    assert L.psd_tune_set(2, 0) == psd.E_INVALID and L.psd_tune_set(-1, 0) == psd.E_INVALID
+    assert L.psd_tune_set(3, 0) == psd.E_INVALID and L.psd_tune_set(-1, 0) == psd.E_INVALID
 
 
 def test_factor_matrices_past_the_32_bit_offset_reach_are_refused_on_the_host():

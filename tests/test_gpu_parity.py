@@ -203,6 +203,16 @@ def test_sfb_bf16_every_tile_shape_bit_exact(tile, M, N, B, P, pinned_tile):
     assert np.array_equal(Mg, Mr) and np.array_equal(Wg, Wr)
 
 
+def test_sfb_bf16_phase_skew_changes_no_bit(pinned_tile):
+    """The measurement aid that starts half of the chip's first workgroups late only shifts work in time."""
+    pinned_tile(psd.TUNE_SFB_BF16_SKEW_US, 15)
+    d = inputs.fc_layer_integer(M=1500, N=2100, B=40, P=5, seed=58)        # 17 x 8 tiles of 128 x 192
+    Wg, Mg, _ = run_sfb(d, psd.BF16, 0.25, 0.5)
+    U, V = orc.pack_factors(d["delta"], d["act"])
+    Wr, Mr = orc.sync_fc_sfb(U, V, d["W"], d["Mom"], 0.25, 0.5)
+    assert np.array_equal(Mg, Mr) and np.array_equal(Wg, Wr)
+
+
 @pytest.mark.parametrize("tile", [1, 2])
 def test_sfb_f32_both_tile_shapes_bit_exact(tile, pinned_tile):
     pinned_tile(psd.TUNE_SFB_F32_TILE, tile)
