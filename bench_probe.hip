@@ -3,6 +3,7 @@
 //     hipcc --offload-arch=gfx950 -O3 -Xclang -target-feature -Xclang -packed-fp32-ops bench_probe.hip -o bench_probe
 //     ./bench_probe stream          # bare streams: what HBM gives a "P reads + read-modify-write of two arrays" pattern
 //     ./bench_probe coresident      # MFMA-only workgroups and streaming workgroups sharing the compute units
+//     ./bench_probe xcd             # the same read-modify-write stream from the CUs of 1, 2, 4 or all 8 XCDs only
 // Every access is bounds-checked by construction (fixed sizes below); every loop has a fixed trip count.
 #include <hip/hip_runtime.h>
 #include <cstdio>
@@ -167,6 +168,73 @@ static void run_coresident(hipEvent_t e0, hipEvent_t e1)
         }
 }
 
+// ---------------------------------------------------------------------------------------------------
+// xcd: every workgroup owns a slice of W and Mom; only those that find themselves on an XCD of the
+// given set stream it (read-modify-write), the others leave at once.  What can ONE accelerator die
+// pull from memory when the other seven are idle?
+// ---------------------------------------------------------------------------------------------------
+__global__ void __launch_bounds__(256, 2) xcd_stream(float* __restrict__ W, float* __restrict__ Mom, unsigned xcd_set, Rec* rec)
+{
+    extern __shared__ float dummy[];     // 70000 bytes asked for at launch: at most two workgroups per CU
+    const long long w0 = wall_clock64();
+    const unsigned xcc = __builtin_amdgcn_s_getreg((31 << 11) | (0 << 6) | 20) & 15;
+    const bool active = (xcd_set >> xcc) & 1;
+    if (active) {
+        float4* w4 = reinterpret_cast<float4*>(W) + size_t(blockIdx.x) * N4;       // blockIdx.x < 512: inside the arrays
+        float4* m4 = reinterpret_cast<float4*>(Mom) + size_t(blockIdx.x) * N4;
+        for (size_t i = threadIdx.x; i < N4; i += 256 * 4) {                       // N4 = 144 * 1024: i + 768 < N4
+            float4 w[4], m[4];
+#pragma unroll
+            for (int u = 0; u < 4; ++u) { w[u] = w4[i + u * 256]; m[u] = m4[i + u * 256]; }
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                m[u].x = 0.9f * m[u].x + 0.01f; m[u].y = 0.9f * m[u].y + 0.01f; m[u].z = 0.9f * m[u].z + 0.01f; m[u].w = 0.9f * m[u].w + 0.01f;
+                w[u].x -= m[u].x; w[u].y -= m[u].y; w[u].z -= m[u].z; w[u].w -= m[u].w;
+                m4[i + u * 256] = m[u]; w4[i + u * 256] = w[u];
+            }
+        }
+    }
+    if (xcd_set == 0xffffffffu) dummy[threadIdx.x] = 0;
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        Rec r;
+        r.hwid = __builtin_amdgcn_s_getreg((31 << 11) | (0 << 6) | 4);
+        r.xcc = xcc | (active ? 0x100 : 0);
+        r.t0 = w0; r.t1 = wall_clock64(); r.cyc = 0;
+        rec[blockIdx.x] = r;
+    }
+}
+
+static void run_xcd(hipEvent_t e0, hipEvent_t e1)
+{
+    const int max_grid = 512;
+    const size_t n = size_t(max_grid) * N4 * 4;
+    float *W, *Mom; CK(hipMalloc(&W, n * 4)); CK(hipMalloc(&Mom, n * 4)); CK(hipMemset(W, 0, n * 4)); CK(hipMemset(Mom, 0, n * 4));
+    CK(hipFuncSetAttribute((const void*)xcd_stream, hipFuncAttributeMaxDynamicSharedMemorySize, 140000));
+    Rec* rec; CK(hipMalloc(&rec, max_grid * sizeof(Rec)));
+    const unsigned sets[] = {0xff, 0x01, 0x10, 0x03, 0x0f, 0x55, 0xff};
+    for (int grid : {256, 512})
+        for (int rep = 0; rep < 2; ++rep)
+            for (unsigned set : sets) {
+                float ms;
+                CK(hipDeviceSynchronize()); CK(hipEventRecord(e0));
+                xcd_stream<<<grid, 256, 70000>>>(W, Mom, set, rec);
+                CK(hipEventRecord(e1)); CK(hipEventSynchronize(e1)); CK(hipEventElapsedTime(&ms, e0, e1));
+                if (rep == 0) continue;                                  // first round: clocks settling
+                std::vector<Rec> h(grid); CK(hipMemcpy(h.data(), rec, grid * sizeof(Rec), hipMemcpyDeviceToHost));
+                int active = 0; long long t0 = 0, t1 = 0; std::map<unsigned, int> cus;
+                for (auto& x : h) if (x.xcc & 0x100) {
+                    if (!active || x.t0 < t0) t0 = x.t0;
+                    if (!active || x.t1 > t1) t1 = x.t1;
+                    ++active; cus[((x.xcc & 15) << 16) | (x.hwid & 0xff00)]++;
+                }
+                const double us = (t1 - t0) / 100.0, bytes = double(active) * N4 * 16 * 4;      // two arrays, read and written
+                int nx = 0; for (int b = 0; b < 8; ++b) nx += (set >> b) & 1;
+                printf("  XCD set 0x%02x (%d XCDs), %3d workgroups launched: %3d stream on %3d CUs, %7.1f us from first start to last end = %6.0f GB/s, %5.0f GB/s per XCD (event time %7.1f us)\n",
+                       set, nx, grid, active, (int)cus.size(), us, bytes / us / 1e3, bytes / us / 1e3 / nx, ms * 1e3);
+            }
+}
+
 int main(int argc, char** argv)
 {
     hipEvent_t e0, e1; CK(hipEventCreate(&e0)); CK(hipEventCreate(&e1));
@@ -180,8 +248,11 @@ int main(int argc, char** argv)
     } else if (!strcmp(what, "coresident")) {
         printf("one launch, two kinds of workgroups (each 256 lanes, at most two per CU); times per workgroup from the 100 MHz clock:\n");
         run_coresident(e0, e1);
+    } else if (!strcmp(what, "xcd")) {
+        printf("read-modify-write stream of two arrays (2.36 MB per array and workgroup) from the CUs of a subset of the XCDs:\n");
+        run_xcd(e0, e1);
     } else {
-        printf("usage: bench_probe stream|coresident\n");
+        printf("usage: bench_probe stream|coresident|xcd\n");
         return 2;
     }
     return 0;
