@@ -104,6 +104,10 @@ psd_status psd_pack_factors(const psd_plan* plan, const float* const* delta_p,
  * fp32 factors: fp32 MFMA, fp32 accumulation.  bf16 factors: bf16 MFMA with fp32
  * accumulation; W and Mom stay fp32.  The same call serves the SF_PS route (the server
  * runs the identical reconstruction over the same P*B factors).
+ * Size limit: the kernels address each stacked factor matrix with 32-bit byte offsets, so K * ldu and
+ * K * ldv times the element size must stay below 4 GiB less a few k-stages of read-ahead (the largest
+ * layer named in the paper, a VGG-16-sized 25088 -> 4096 one at K = 2048, needs 0.2 GiB); a larger
+ * layer is refused with PSD_E_UNSUPPORTED before anything is launched.
  *
  * workspace [dev] (optional): scratch for layers with so few output tiles (128 x 128 weights each)
  * that most compute units would get none (e.g. a 1024 -> 1000 classifier).  With workspace_bytes == 0 (workspace may be NULL) every tile is contracted
