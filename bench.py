@@ -173,6 +173,7 @@ class Leg:
         fc_dtype = psd.BF16 if fc_dtype_name == "bf16" else psd.F32
         self.sets = build_device_sets(layers, fc_dtype, n_sets, psd, torch, dev, one_stream)
         self.n_sets = n_sets
+        self.blocks_in_place = False     # fp32 only: FC layers handed over without stacked buffers (no pack launch)
         self.work = [layer_work(L, fc_dtype_name) for L in layers]
         self.kinds = [psd.LAYER_CONV if L["kind"] == "conv" else psd.LAYER_FC for L in layers]
         self.dims = [(L["n"], 1) if L["kind"] == "conv" else (L["M"], L["N"]) for L in layers]
@@ -200,6 +201,10 @@ class Leg:
         iters, marks = [], []
         for i in range(total):
             tasks = [dict(t) for t in self.sets[i % self.n_sets]]
+            if self.blocks_in_place:
+                for t in tasks:
+                    if t["kind"] == "fc" and t["factor_dtype"] == psd.F32 and psd.sfb_blocks_supported(t["plan"]):
+                        t.update(U=None, V=None)
             if dependent:
                 for t in tasks:
                     t["ev_ready"] = self.ev_step_done   # "the iteration before has finished on every stream"
@@ -449,6 +454,11 @@ def main():
                        "roofline": roofline_of(leg2, dur2, layers, other),
                        "per_layer_median_ms": {L["name"]: round(float(np.median(dur2[:, j])), 5)
                                                for j, L in enumerate(layers)}}
+        if other == "f32":
+            # the same step with the fp32 factor blocks read where they lie (psd_sync_fc_sfb_blocks): no pack launches
+            leg2.blocks_in_place = True
+            ms3, _ = leg2.run(args.steps, args.warmup, dependent=False)
+            side[other]["ms_per_step_blocks_read_in_place"] = round(ms3, 4)
         del leg2
         torch.cuda.empty_cache()
         import bench_extras

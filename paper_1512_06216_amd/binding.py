@@ -86,6 +86,9 @@ SIGNATURES = {
     "psd_sync_fc_sfb_static": (ctypes.c_int32, [ctypes.POINTER(Plan), ctypes.c_int32, ctypes.c_void_p, ctypes.c_int64,
                                                 ctypes.c_void_p, ctypes.c_int64, ctypes.c_void_p, ctypes.c_void_p,
                                                 ctypes.c_float, ctypes.c_float, ctypes.c_float, ctypes.c_void_p]),
+    "psd_sfb_blocks_supported": (ctypes.c_int32, [ctypes.POINTER(Plan)]),
+    "psd_sync_fc_sfb_blocks": (ctypes.c_int32, [ctypes.POINTER(Plan), _f32pp, _f32pp, ctypes.c_void_p, ctypes.c_void_p,
+                                                ctypes.c_float, ctypes.c_float, ctypes.c_float, ctypes.c_void_p]),
     "psd_sync_fc_bias": (ctypes.c_int32, [ctypes.POINTER(Plan), ctypes.c_int32, ctypes.c_void_p, ctypes.c_int64,
                                           ctypes.c_void_p, ctypes.c_void_p, ctypes.c_float, ctypes.c_float,
                                           ctypes.c_float, ctypes.c_void_p]),
@@ -248,6 +251,22 @@ def sync_fc_sfb_static(plan, factor_dtype, U, ldu, V, ldv, W, Mom, lr, mu, strea
                                         _stream_handle(stream)), "psd_sync_fc_sfb_static")
 
 
+def sfb_blocks_supported(plan):
+    return bool(lib().psd_sfb_blocks_supported(ctypes.byref(plan)))
+
+
+def sync_fc_sfb_blocks(plan, delta, act, W, Mom, lr, mu, stream=None, wd=0.0):
+    """fp32 reconstruction + update straight from the P per-worker blocks (no stacked copy)."""
+    if len(delta) != plan.P or len(act) != plan.P:
+        raise ValueError("need P per-worker blocks")
+    d = _ptr_array(delta, plan.B * plan.N, "delta")
+    a = _ptr_array(act, plan.B * plan.M, "act")
+    wp = _dev_ptr(W, torch.float32, plan.N * plan.M, "W")
+    mp = _dev_ptr(Mom, torch.float32, plan.N * plan.M, "Mom")
+    _check(lib().psd_sync_fc_sfb_blocks(ctypes.byref(plan), d, a, wp, mp, lr, mu, wd, _stream_handle(stream)),
+           "psd_sync_fc_sfb_blocks")
+
+
 def sync_fc_bias(plan, factor_dtype, U, ldu, bias, mom_bias, lr, mu, stream=None, wd=0.0):
     up = _dev_ptr(U, _FACTOR_TORCH.get(factor_dtype, ()), plan.K * ldu, "U")
     bp = _dev_ptr(bias, torch.float32, plan.N, "bias")
@@ -356,6 +375,7 @@ class Iteration:
     """Marshalled, reusable argument block for psd_sync_iteration (layers bottom-up).
 
     Each layer is a dict: FC  -> plan, factor_dtype, delta, act, U, ldu, V, ldv, W, Mom, stream[, workspace]
+                                 (U = V = None with fp32 factors: the blocks are read in place, nothing is stacked)
                          conv -> plan, G, S, W, Mom, stream
     plus optional ev_ready (the layer's stream waits for it first) and ev_begin / ev_end (recorded
     around the layer's sync kernel); all raw hipEvent_t handles as ints.
@@ -389,8 +409,9 @@ class Iteration:
                 self._keep += [d, a]
                 t.delta_p, t.act_p = ctypes.cast(d, _f32pp), ctypes.cast(a, _f32pp)
                 fd = _FACTOR_TORCH.get(t.factor_dtype, ())
-                t.U, t.ldu = _dev_ptr(L["U"], fd, plan.K * L["ldu"], "U"), L["ldu"]
-                t.V, t.ldv = _dev_ptr(L["V"], fd, plan.K * L["ldv"], "V"), L["ldv"]
+                if L.get("U") is not None or L.get("V") is not None:      # neither: fp32 blocks read in place
+                    t.U, t.ldu = _dev_ptr(L["U"], fd, plan.K * L["ldu"], "U"), L["ldu"]
+                    t.V, t.ldv = _dev_ptr(L["V"], fd, plan.K * L["ldv"], "V"), L["ldv"]
         self.L = len(layers)
 
     def run(self, lr, mu, rule=RULE_ALG3, wd=0.0):

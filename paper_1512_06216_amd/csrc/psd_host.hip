@@ -194,6 +194,27 @@ psd_status psd_sync_fc_sfb(const psd_plan* plan, int32_t factor_dtype, const voi
                            plan->N, plan->M, K, lr, mu, wd, part, splits, st);
 }
 
+int32_t psd_sfb_blocks_supported(const psd_plan* plan)
+{
+    return plan && valid_plan_sizes(plan) && sfb_f32_blocks_supported(plan->N, plan->M, plan->B) ? 1 : 0;
+}
+
+psd_status psd_sync_fc_sfb_blocks(const psd_plan* plan, const float* const* delta_p, const float* const* act_p,
+                                  float* W, float* Mom, float lr, float mu, float wd, void* stream)
+{
+    if (!plan || !delta_p || !act_p || !W || !Mom) return PSD_E_NULL;
+    if (!(wd >= 0.0f)) return PSD_E_INVALID;          // also rejects NaN
+    if (!valid_plan_sizes(plan)) return PSD_E_INVALID;
+    if (!aligned16(W) || !aligned16(Mom) || W == Mom) return PSD_E_INVALID;
+    for (int64_t p = 0; p < plan->P; ++p) {
+        if (!delta_p[p] || !act_p[p]) return PSD_E_NULL;
+        if (!aligned16(delta_p[p]) || !aligned16(act_p[p])) return PSD_E_INVALID;
+    }
+    if (!sfb_f32_blocks_supported(plan->N, plan->M, plan->B)) return PSD_E_UNSUPPORTED;
+    return launch_sfb_f32_blocks(delta_p, act_p, plan->P, plan->B, W, Mom, plan->N, plan->M, lr, mu, wd,
+                                 static_cast<hipStream_t>(stream));
+}
+
 psd_status psd_sync_fc_bias(const psd_plan* plan, int32_t factor_dtype, const void* U, int64_t ldu, float* bias,
                             float* mom_bias, float lr, float mu, float wd, void* stream)
 {
@@ -358,11 +379,17 @@ psd_status psd_sync_iteration(int32_t L, const psd_layer_task* layers, float lr,
                                   lr, mu, wd, t.S, t.stream);
         } else if (route == PSD_ROUTE_SFB || route == PSD_ROUTE_SF_PS) {
             if (t.plan.kind != PSD_LAYER_FC) return PSD_E_INVALID;
-            r = psd_pack_factors(&t.plan, t.delta_p, t.act_p, t.factor_dtype, t.U, t.ldu, t.V, t.ldv, t.stream);
-            if (r == PSD_OK && t.ev_begin) PSD_HIP_TRY(hipEventRecord(static_cast<hipEvent_t>(t.ev_begin), st));
-            if (r == PSD_OK)
-                r = psd_sync_fc_sfb(&t.plan, t.factor_dtype, t.U, t.ldu, t.V, t.ldv, t.W, t.Mom, lr, mu, wd, t.workspace,
-                                    t.workspace_bytes, t.stream);
+            if (!t.U && !t.V && t.factor_dtype == PSD_F32) {
+                // no stacked buffers given: the fp32 blocks are read where they lie
+                if (t.ev_begin) PSD_HIP_TRY(hipEventRecord(static_cast<hipEvent_t>(t.ev_begin), st));
+                r = psd_sync_fc_sfb_blocks(&t.plan, t.delta_p, t.act_p, t.W, t.Mom, lr, mu, wd, t.stream);
+            } else {
+                r = psd_pack_factors(&t.plan, t.delta_p, t.act_p, t.factor_dtype, t.U, t.ldu, t.V, t.ldv, t.stream);
+                if (r == PSD_OK && t.ev_begin) PSD_HIP_TRY(hipEventRecord(static_cast<hipEvent_t>(t.ev_begin), st));
+                if (r == PSD_OK)
+                    r = psd_sync_fc_sfb(&t.plan, t.factor_dtype, t.U, t.ldu, t.V, t.ldv, t.W, t.Mom, lr, mu, wd,
+                                        t.workspace, t.workspace_bytes, t.stream);
+            }
         } else {
             return PSD_E_INVALID;
         }

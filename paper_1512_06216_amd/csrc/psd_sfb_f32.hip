@@ -38,13 +38,29 @@ constexpr int NSTAGE = 4;           // ring depth
 // (tile, s) contracts over k-stages [s * stages_per_split, (s+1) * stages_per_split) and stores its
 // partial dW tile to part + s * part_stride (N x M row-major); the partials are summed in split order
 // and the update applied by the parameter-server sum kernel afterwards.
-template <int BN, bool PART>
-__global__ void __launch_bounds__(THREADS)
-sfb_f32_kernel(const float* __restrict__ U, int64_t ldu, const float* __restrict__ V, int64_t ldv,
-               float* __restrict__ W, float* __restrict__ Mom, int N, int M, int K, float lr, float mu, float wd,
-               int tiles_m, int tiles, uint32_t u_bytes, uint32_t v_bytes, float* __restrict__ part,
-               int64_t part_stride, int stages_per_split)
+// BLK = true: the factors are not stacked.  Row k = p*B + b of U is row b of the p-th worker's B x N block
+// (V likewise, B x M), read where it lies: a stage of KT rows never straddles two blocks because KT divides
+// B, so the only difference is that the buffer descriptor is re-aimed whenever the stages move on to the
+// next block (and aimed at nothing past the last one, which reads as zeros like the K tail does).
+struct BlockPtrs { const float* u[PSD_MAX_WORKERS]; const float* v[PSD_MAX_WORKERS]; };
+
+// a pointer every lane holds alike, moved to scalar registers (buffer descriptors live there)
+__device__ __forceinline__ const float* uniform_ptr(const float* p)
 {
+    const uint64_t a = reinterpret_cast<uint64_t>(p);
+    const uint32_t lo = __builtin_amdgcn_readfirstlane(static_cast<uint32_t>(a));
+    const uint32_t hi = __builtin_amdgcn_readfirstlane(static_cast<uint32_t>(a >> 32));
+    return reinterpret_cast<const float*>((static_cast<uint64_t>(hi) << 32) | lo);
+}
+
+template <int BN, bool PART, bool BLK>
+__device__ __forceinline__ void
+sfb_f32_body(const float* __restrict__ U, int64_t ldu, const float* __restrict__ V, int64_t ldv,
+             float* __restrict__ W, float* __restrict__ Mom, int N, int M, int K, float lr, float mu, float wd,
+             int tiles_m, int tiles, uint32_t u_bytes, uint32_t v_bytes, float* __restrict__ part,
+             int64_t part_stride, int stages_per_split, const BlockPtrs* blocks, int n_blocks, int stages_per_block)
+{
+    static_assert(!(PART && BLK), "blocks read in place are not combined with a split of K");
     constexpr int TN = 64 * BN;
     constexpr int RA = TN * 4, RB = TM * 4;                       // LDS row bytes
     constexpr int A_BYTES = KT * RA, B_BYTES = KT * RB, STAGE_BYTES = A_BYTES + B_BYTES;
@@ -72,7 +88,15 @@ sfb_f32_kernel(const float* __restrict__ U, int64_t ldu, const float* __restrict
     const int l32 = lane & 31, lhi = lane >> 5;
 
     // DMA plan: run j of this wavefront covers chunks f = (wave*NI + j)*64 + lane of the stage
-    const i32x4 rsrc_u = raw_rsrc(U, u_bytes), rsrc_v = raw_rsrc(V, v_bytes);
+    i32x4 rsrc_u = raw_rsrc(U, u_bytes), rsrc_v = raw_rsrc(V, v_bytes);
+    int blk = 0, stage_in_blk = 0;               // BLK: where the next stage to be requested lies
+    auto aim_block = [&]() {                     // BLK: descriptors over block `blk` (u_bytes, v_bytes = one block)
+        const bool live = blk < n_blocks;
+        const int i = live ? blk : 0;            // the table is never indexed past its end
+        rsrc_u = raw_rsrc(uniform_ptr(blocks->u[i]), live ? u_bytes : 0u);
+        rsrc_v = raw_rsrc(uniform_ptr(blocks->v[i]), live ? v_bytes : 0u);
+    };
+    if constexpr (BLK) aim_block();
     uint32_t voff_a[NI_A], voff_b[NI_B];
 #pragma unroll
     for (int j = 0; j < NI_A; ++j) {
@@ -87,12 +111,20 @@ sfb_f32_kernel(const float* __restrict__ U, int64_t ldu, const float* __restrict
     const uint32_t step_a = static_cast<uint32_t>(KT * ldu * 4), step_b = static_cast<uint32_t>(KT * ldv * 4);
     auto issue = [&](int t) {                    // stage t -> ring buffer t % NSTAGE; past K: zeros
         const uint32_t base = lds0 + static_cast<uint32_t>(t % NSTAGE) * STAGE_BYTES;
+        const uint32_t s = static_cast<uint32_t>(BLK ? stage_in_blk : t);     // stages are requested in order
 #pragma unroll
         for (int j = 0; j < NI_A; ++j)
-            dma_b128(base + (wave * NI_A + j) * 1024, voff_a[j] + static_cast<uint32_t>(t) * step_a, rsrc_u);
+            dma_b128(base + (wave * NI_A + j) * 1024, voff_a[j] + s * step_a, rsrc_u);
 #pragma unroll
         for (int j = 0; j < NI_B; ++j)
-            dma_b128(base + A_BYTES + (wave * NI_B + j) * 1024, voff_b[j] + static_cast<uint32_t>(t) * step_b, rsrc_v);
+            dma_b128(base + A_BYTES + (wave * NI_B + j) * 1024, voff_b[j] + s * step_b, rsrc_v);
+        if constexpr (BLK) {
+            if (++stage_in_blk == stages_per_block) {
+                stage_in_blk = 0;
+                ++blk;
+                aim_block();
+            }
+        }
     };
 
     f32x16 acc[BN][2];
@@ -203,6 +235,28 @@ sfb_f32_kernel(const float* __restrict__ U, int64_t ldu, const float* __restrict
     }
 }
 
+template <int BN, bool PART>
+__global__ void __launch_bounds__(THREADS)
+sfb_f32_kernel(const float* __restrict__ U, int64_t ldu, const float* __restrict__ V, int64_t ldv,
+               float* __restrict__ W, float* __restrict__ Mom, int N, int M, int K, float lr, float mu, float wd,
+               int tiles_m, int tiles, uint32_t u_bytes, uint32_t v_bytes, float* __restrict__ part,
+               int64_t part_stride, int stages_per_split)
+{
+    sfb_f32_body<BN, PART, false>(U, ldu, V, ldv, W, Mom, N, M, K, lr, mu, wd, tiles_m, tiles, u_bytes, v_bytes, part,
+                                  part_stride, stages_per_split, nullptr, 0, 0);
+}
+
+// the P per-worker blocks read in place (u_bytes, v_bytes: the size of ONE block)
+template <int BN>
+__global__ void __launch_bounds__(THREADS)
+sfb_f32_blocks_kernel(BlockPtrs blocks, int n_blocks, int stages_per_block, float* __restrict__ W,
+                      float* __restrict__ Mom, int N, int M, int K, float lr, float mu, float wd, int tiles_m,
+                      int tiles, uint32_t u_bytes, uint32_t v_bytes)
+{
+    sfb_f32_body<BN, false, true>(nullptr, N, nullptr, M, W, Mom, N, M, K, lr, mu, wd, tiles_m, tiles, u_bytes, v_bytes,
+                                  nullptr, 0, 0, &blocks, n_blocks, stages_per_block);
+}
+
 template <int BN>
 psd_status launch_f32(const float* U, int64_t ldu, const float* V, int64_t ldv, float* W, float* Mom,
                       int64_t N, int64_t M, int64_t K, float lr, float mu, float wd, float* part, int splits,
@@ -225,6 +279,24 @@ psd_status launch_f32(const float* U, int64_t ldu, const float* V, int64_t ldv, 
                        static_cast<uint32_t>(v_bytes), part, sfb_part_stride(N, M), sps);
     PSD_HIP_TRY(hipGetLastError());
     if (splits > 1) return launch_sfb_reduce(part, splits, N, M, W, Mom, lr, mu, wd, st);
+    return PSD_OK;
+}
+
+template <int BN>
+psd_status launch_f32_blocks(const BlockPtrs& blocks, int64_t P, int64_t B, float* W, float* Mom, int64_t N, int64_t M,
+                             float lr, float mu, float wd, hipStream_t st)
+{
+    constexpr int TN = 64 * BN;
+    const int64_t tiles_n = (N + TN - 1) / TN, tiles_m = (M + TM - 1) / TM;
+    const int64_t tiles = tiles_n * tiles_m;
+    if (tiles < 1 || tiles > 0x7fffffff) return PSD_E_INVALID;
+    const int64_t u_bytes = B * N * 4, v_bytes = B * M * 4;            // one block
+    if (u_bytes >= (int64_t(1) << 32) || v_bytes >= (int64_t(1) << 32)) return PSD_E_UNSUPPORTED;
+    hipLaunchKernelGGL(sfb_f32_blocks_kernel<BN>, dim3(static_cast<uint32_t>(tiles)), dim3(THREADS), 0, st, blocks,
+                       static_cast<int>(P), static_cast<int>(B / KT), W, Mom, static_cast<int>(N), static_cast<int>(M),
+                       static_cast<int>(P * B), lr, mu, wd, static_cast<int>(tiles_m), static_cast<int>(tiles),
+                       static_cast<uint32_t>(u_bytes), static_cast<uint32_t>(v_bytes));
+    PSD_HIP_TRY(hipGetLastError());
     return PSD_OK;
 }
 
@@ -261,6 +333,27 @@ psd_status launch_sfb_f32(const float* U, int64_t ldu, const float* V, int64_t l
     choose_f32(N, M, K, splits > 1, &bn, &s);
     if (bn == 1) return launch_f32<1>(U, ldu, V, ldv, W, Mom, N, M, K, lr, mu, wd, part, splits, st);
     return launch_f32<2>(U, ldu, V, ldv, W, Mom, N, M, K, lr, mu, wd, part, splits, st);
+}
+
+bool sfb_f32_blocks_supported(int64_t N, int64_t M, int64_t B)
+{
+    // whole stages per block, and every row of every block starts on a 16-byte boundary
+    return B % KT == 0 && N % 4 == 0 && M % 4 == 0;
+}
+
+psd_status launch_sfb_f32_blocks(const float* const* delta_p, const float* const* act_p, int64_t P, int64_t B,
+                                 float* W, float* Mom, int64_t N, int64_t M, float lr, float mu, float wd, hipStream_t st)
+{
+    if (P < 1 || P > PSD_MAX_WORKERS || !sfb_f32_blocks_supported(N, M, B)) return PSD_E_UNSUPPORTED;
+    BlockPtrs blocks;
+    for (int64_t p = 0; p < PSD_MAX_WORKERS; ++p) {
+        blocks.u[p] = p < P ? delta_p[p] : nullptr;
+        blocks.v[p] = p < P ? act_p[p] : nullptr;
+    }
+    int bn, s;
+    choose_f32(N, M, P * B, false, &bn, &s);
+    if (bn == 1) return launch_f32_blocks<1>(blocks, P, B, W, Mom, N, M, lr, mu, wd, st);
+    return launch_f32_blocks<2>(blocks, P, B, W, Mom, N, M, lr, mu, wd, st);
 }
 
 }  // namespace psd

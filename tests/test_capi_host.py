@@ -262,3 +262,31 @@ def test_ssp_clock_bookkeeping_against_a_literal_ring():
     assert L.psd_ssp_init(ctypes.byref(st), -1) == psd.E_INVALID
     assert L.psd_ssp_init(ctypes.byref(st), psd.MAX_STALENESS + 1) == psd.E_INVALID
     assert L.psd_ssp_slots(ctypes.byref(st), None, None) == psd.E_NULL
+
+
+def test_blocks_in_place_support_rule_and_argument_checks():
+    """Which layers the fp32 reconstruction can read straight from the per-worker blocks, and what the entry
+    point says about bad arguments -- all decided on the host before anything is launched."""
+    L = psd.lib()
+    for (M, N, B, P), ok in (((4096, 1000, 256, 8), True), ((9216, 4096, 16, 64), True), ((256, 128, 11, 4), False),
+                             ((256, 130, 16, 4), False), ((4096, 21841, 256, 8), False), ((258, 128, 32, 4), False)):
+        plan = psd.plan_layer(psd.LAYER_FC, M, N, B, P)
+        assert bool(L.psd_sfb_blocks_supported(ctypes.byref(plan))) == ok
+    assert L.psd_sfb_blocks_supported(None) == 0
+    plan = psd.plan_layer(psd.LAYER_FC, 256, 130, 16, 2)           # unsupported shape: nothing is ever launched
+    fake = 0x10000000
+    ptrs = (ctypes.POINTER(ctypes.c_float) * 2)(*[ctypes.cast(fake + 0x100000 * i, ctypes.POINTER(ctypes.c_float)) for i in range(2)])
+    pp = ctypes.cast(ptrs, ctypes.POINTER(ctypes.POINTER(ctypes.c_float)))
+    call = lambda *a: L.psd_sync_fc_sfb_blocks(*a)
+    W, Mom = ctypes.c_void_p(fake + 0x800000), ctypes.c_void_p(fake + 0x900000)
+    assert call(ctypes.byref(plan), pp, pp, W, Mom, 0.1, 0.9, 0.0, None) == psd.E_UNSUPPORTED
+    assert call(None, pp, pp, W, Mom, 0.1, 0.9, 0.0, None) == psd.E_NULL
+    assert call(ctypes.byref(plan), None, pp, W, Mom, 0.1, 0.9, 0.0, None) == psd.E_NULL
+    assert call(ctypes.byref(plan), pp, pp, None, Mom, 0.1, 0.9, 0.0, None) == psd.E_NULL
+    assert call(ctypes.byref(plan), pp, pp, W, W, 0.1, 0.9, 0.0, None) == psd.E_INVALID
+    assert call(ctypes.byref(plan), pp, pp, ctypes.c_void_p(fake + 4), Mom, 0.1, 0.9, 0.0, None) == psd.E_INVALID
+    assert call(ctypes.byref(plan), pp, pp, W, Mom, 0.1, 0.9, -1.0, None) == psd.E_INVALID
+    ptrs[1] = ctypes.cast(fake + 8, ctypes.POINTER(ctypes.c_float))
+    assert call(ctypes.byref(plan), pp, pp, W, Mom, 0.1, 0.9, 0.0, None) == psd.E_INVALID
+    ptrs[1] = ctypes.cast(None, ctypes.POINTER(ctypes.c_float))
+    assert call(ctypes.byref(plan), pp, pp, W, Mom, 0.1, 0.9, 0.0, None) == psd.E_NULL

@@ -516,6 +516,78 @@ def test_bias_full_size_configs(cfg, dtype):
     assert orc.rel_frob(bias.cpu().numpy(), br) <= TOL_F32
 
 
+BLOCK_SHAPES = [  # M, N, B, P with B a multiple of 16 and N, M multiples of 4
+    (256, 128, 32, 4),        # config 1
+    (520, 300, 16, 5),        # ragged tiles both ways, one k-stage per block
+    (132, 64, 48, 3),         # three stages per block, blocks exhausted mid ring: the trailing stages must read as zeros
+    (260, 204, 16, 64),       # the largest worker count: every entry of the pointer table in use
+]
+
+
+@pytest.mark.parametrize("M,N,B,P", BLOCK_SHAPES)
+def test_sfb_blocks_in_place_bit_exact_and_identical_to_the_stacked_path(M, N, B, P):
+    """fp32 reconstruction straight from the P per-worker blocks: bit-exact against the oracle on integer
+    data, and on Gaussian data the very bits of pack + reconstruct (same arithmetic, same order)."""
+    d = inputs.fc_layer_integer(M=M, N=N, B=B, P=P, seed=M + P, amax=2 if B * P > 500 else 3)
+    plan = psd.plan_layer(psd.LAYER_FC, M, N, B, P)
+    assert psd.sfb_blocks_supported(plan)
+    W, Mom = dev(d["W"]), dev(d["Mom"])
+    psd.sync_fc_sfb_blocks(plan, [dev(x) for x in d["delta"]], [dev(x) for x in d["act"]], W, Mom, 0.25, 0.5, wd=0.5)
+    torch.cuda.synchronize()
+    U, V = orc.pack_factors(d["delta"], d["act"])
+    Wr, Mr = orc.sync_fc_sfb(U, V, d["W"], d["Mom"], 0.25, 0.5, wd=0.5)
+    assert np.array_equal(Mom.cpu().numpy(), Mr) and np.array_equal(W.cpu().numpy(), Wr)
+
+    g = inputs.fc_layer(M=M, N=N, B=B, P=P, seed=M + 2 * P, mom_std=1e-4)
+    Ws, Ms, _ = run_sfb(g, psd.F32, inputs.LR, inputs.MU)
+    W, Mom = dev(g["W"]), dev(g["Mom"])
+    psd.sync_fc_sfb_blocks(plan, [dev(x) for x in g["delta"]], [dev(x) for x in g["act"]], W, Mom, inputs.LR, inputs.MU)
+    torch.cuda.synchronize()
+    assert np.array_equal(Mom.cpu().numpy(), Ms) and np.array_equal(W.cpu().numpy(), Ws)
+
+
+def test_sfb_blocks_in_place_at_the_classifier_size():
+    """Config 2 (4096 -> 1000, K = 2048, fp32) without the stacking pass: whole matrix against the oracle."""
+    d = inputs.fc_config(2)
+    plan = psd.plan_layer(psd.LAYER_FC, d["M"], d["N"], d["B"], d["P"])
+    W, Mom = dev(d["W"]), dev(d["Mom"])
+    psd.sync_fc_sfb_blocks(plan, [dev(x) for x in d["delta"]], [dev(x) for x in d["act"]], W, Mom, inputs.LR, inputs.MU)
+    torch.cuda.synchronize()
+    _whole_matrix_checks(d, W.cpu().numpy(), Mom.cpu().numpy(), "f32", inputs.LR, inputs.MU)
+
+
+@pytest.mark.parametrize("M,N,B,P", [(256, 128, 11, 4), (256, 130, 16, 4), (21841, 64, 16, 2)])
+def test_sfb_blocks_in_place_refuses_layers_it_cannot_read(M, N, B, P):
+    # a k-stage would straddle two blocks (B), or rows of a block would not be 16-byte aligned (N, M)
+    plan = psd.plan_layer(psd.LAYER_FC, M, N, B, P)
+    assert not psd.sfb_blocks_supported(plan)
+    W, Mom = torch.zeros(N, M, device=DEV), torch.zeros(N, M, device=DEV)
+    delta = [torch.zeros(B, N, device=DEV) for _ in range(P)]
+    act = [torch.zeros(B, M, device=DEV) for _ in range(P)]
+    with pytest.raises(psd.PsdError) as e:
+        psd.sync_fc_sfb_blocks(plan, delta, act, W, Mom, 0.01, 0.9)
+    assert e.value.status == psd.E_UNSUPPORTED
+
+
+def test_iteration_reads_fp32_blocks_in_place_when_no_stacked_buffers_are_given():
+    layers = inputs.cnn_iteration(scale=8, B=16, P=4)
+    out = []
+    for in_place in (False, True):
+        tasks, state = _build_iteration(layers, psd.F32, [None] * len(layers))
+        if in_place:
+            switched = 0
+            for t in tasks:
+                if "delta" in t and psd.sfb_blocks_supported(t["plan"]):     # the 512 -> 125 layer keeps its stacked buffers
+                    t.update(U=None, V=None, ldu=0, ldv=0)
+                    switched += 1
+            assert switched == 2
+        psd.Iteration(tasks).run(inputs.LR, inputs.MU, psd.RULE_ALG3)
+        torch.cuda.synchronize()
+        out.append([(W.cpu().numpy(), Mom.cpu().numpy()) for W, Mom in state])
+    for (w0, m0), (w1, m1) in zip(*out):
+        assert np.array_equal(w0, w1) and np.array_equal(m0, m1)
+
+
 def test_sfb_equals_ps_route_on_the_same_gradients():
     # Section 4.3.1: factors reconstruct the gradient exactly, so both routes agree
     d = inputs.fc_layer_integer(M=300, N=200, B=4, P=3, seed=31)
