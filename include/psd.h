@@ -75,9 +75,12 @@ psd_status psd_plan_layer(int32_t kind, int64_t M, int64_t N, int64_t B, int64_t
  * this is the definition used throughout.  Host only. */
 psd_status psd_shard_range(int64_t n, int32_t S, int32_t s, int64_t* begin, int64_t* end);
 
-/* Leading dimension (in elements) that makes every row of a stacked factor matrix with
- * `cols` columns start on a 16-byte boundary: cols rounded up to a multiple of 4 (f32)
- * or 8 (bf16).  Returns 0 for bad arguments. */
+/* Recommended leading dimension (in elements) of a stacked factor matrix with `cols` columns:
+ * cols rounded up to a multiple of 128 bytes (32 f32 or 64 bf16 elements), so that every row starts
+ * on a cache-line boundary.  The entry points accept any leading dimension >= cols whose rows are a
+ * multiple of 16 bytes (4 f32 / 8 bf16 elements); rows that start mid-line cost the bf16
+ * reconstruction of odd-width layers 3-7 % (a 256-byte tile row then spans three lines, not two).
+ * Returns 0 for bad arguments. */
 int64_t psd_factor_ld(int64_t cols, int32_t dtype);
 
 /* SFB steps 1-2 of Section 4.3.1 seen from the receiving worker: stack the P per-worker

@@ -126,7 +126,7 @@ psd_status psd_shard_range(int64_t n, int32_t S, int32_t s, int64_t* begin, int6
 int64_t psd_factor_ld(int64_t cols, int32_t dtype)
 {
     if (cols < 1 || (dtype != PSD_F32 && dtype != PSD_BF16)) return 0;
-    const int64_t q = dtype == PSD_BF16 ? 8 : 4;
+    const int64_t q = dtype == PSD_BF16 ? 64 : 32;      // 128 bytes
     return (cols + q - 1) / q * q;
 }
 

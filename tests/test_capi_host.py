@@ -82,8 +82,10 @@ def test_shard_range_equals_oracle():
 
 
 def test_factor_ld():
-    assert psd.factor_ld(1000, psd.F32) == 1000 and psd.factor_ld(1001, psd.F32) == 1004
-    assert psd.factor_ld(21841, psd.BF16) == 21848 and psd.factor_ld(4096, psd.BF16) == 4096
+    # rows of 128-byte multiples: 32 fp32 or 64 bf16 elements
+    assert psd.factor_ld(1000, psd.F32) == 1024 and psd.factor_ld(1025, psd.F32) == 1056
+    assert psd.factor_ld(21841, psd.BF16) == 21888 and psd.factor_ld(4096, psd.BF16) == 4096
+    assert psd.factor_ld(1, psd.BF16) == 64 and psd.factor_ld(9216, psd.F32) == 9216
     assert psd.lib().psd_factor_ld(0, psd.F32) == 0 and psd.lib().psd_factor_ld(8, 7) == 0
 
 

@@ -177,6 +177,27 @@ def test_sfb_integer_factors_bit_exact(M, N, B, P, dtype):
     assert np.array_equal(Wg, Wr)
 
 
+@pytest.mark.parametrize("dtype", [psd.F32, psd.BF16])
+def test_sfb_smallest_leading_dimensions_bit_exact(dtype):
+    """Stacked factors whose rows are padded to 16 bytes only (the least the entry points accept, rows then
+    start in the middle of cache lines) instead of the 128 bytes psd_factor_ld recommends."""
+    M, N, B, P = 1001, 333, 9, 5
+    d = inputs.fc_layer_integer(M, N, B, P, seed=77)
+    plan = psd.plan_layer(psd.LAYER_FC, M, N, B, P)
+    q = 4 if dtype == psd.F32 else 8
+    ldu, ldv = (N + q - 1) // q * q, (M + q - 1) // q * q
+    assert (ldu, ldv) != (psd.factor_ld(N, dtype), psd.factor_ld(M, dtype))
+    td = torch.float32 if dtype == psd.F32 else torch.bfloat16
+    U, V = torch.empty(plan.K, ldu, dtype=td, device=DEV), torch.empty(plan.K, ldv, dtype=td, device=DEV)
+    psd.pack_factors(plan, [dev(x) for x in d["delta"]], [dev(x) for x in d["act"]], dtype, U, ldu, V, ldv)
+    W, Mom = dev(d["W"]), dev(d["Mom"])
+    psd.sync_fc_sfb(plan, dtype, U, ldu, V, ldv, W, Mom, 0.25, 0.5)
+    torch.cuda.synchronize()
+    Uo, Vo = orc.pack_factors(d["delta"], d["act"])
+    Wr, Mr = orc.sync_fc_sfb(Uo, Vo, d["W"], d["Mom"], 0.25, 0.5)
+    assert np.array_equal(Mom.cpu().numpy(), Mr) and np.array_equal(W.cpu().numpy(), Wr)
+
+
 @pytest.fixture
 def pinned_tile():
     """Pins a kernel tile through the library's tuning hook and releases it afterwards."""
