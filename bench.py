@@ -84,7 +84,7 @@ class HipEvents:
         self.all = []
 
 
-def build_device_sets(layers, fc_dtype, n_sets, psd, torch, dev, one_stream=False):
+def build_device_sets(layers, fc_dtype, n_sets, psd, torch, dev, one_stream=False, bf16_blocks=False):
     """Uploads `n_sets` independent copies of every layer's buffers (rotated between steps so
     that a step never finds its operands in the 256 MB last-level cache from the step before)."""
     sets = []
@@ -105,12 +105,21 @@ def build_device_sets(layers, fc_dtype, n_sets, psd, torch, dev, one_stream=Fals
             else:
                 plan = psd.plan_layer(psd.LAYER_FC, L["M"], L["N"], L["B"], L["P"])
                 U, ldu, V, ldv = psd.alloc_factors(plan, fc_dtype, dev)
-                tasks.append(dict(name=L["name"], kind="fc", plan=plan, factor_dtype=fc_dtype,
-                                  delta=[torch.from_numpy(x).to(dev) for x in L["delta"]],
-                                  act=[torch.from_numpy(x).to(dev) for x in L["act"]],
-                                  U=U, ldu=ldu, V=V, ldv=ldv, workspace=psd.alloc_workspace(plan, fc_dtype, dev),
-                                  W=torch.from_numpy(L["W"]).to(dev), Mom=torch.from_numpy(L["Mom"]).to(dev),
-                                  stream=st))
+                t = dict(name=L["name"], kind="fc", plan=plan, factor_dtype=fc_dtype,
+                         delta=[torch.from_numpy(x).to(dev) for x in L["delta"]],
+                         act=[torch.from_numpy(x).to(dev) for x in L["act"]],
+                         U=U, ldu=ldu, V=V, ldv=ldv, workspace=psd.alloc_workspace(plan, fc_dtype, dev),
+                         W=torch.from_numpy(L["W"]).to(dev), Mom=torch.from_numpy(L["Mom"]).to(dev), stream=st)
+                if bf16_blocks and fc_dtype == psd.BF16:
+                    # the factors as P senders that round before sending would deliver them: one bf16 block per worker
+                    one = psd.plan_layer(psd.LAYER_FC, L["M"], L["N"], L["B"], 1)
+                    t["one"], t["U_blocks"], t["V_blocks"] = one, [], []
+                    for p in range(L["P"]):
+                        Ub, _, Vb, _ = psd.alloc_factors(one, psd.BF16, dev)
+                        psd.pack_factors(one, [t["delta"][p]], [t["act"][p]], psd.BF16, Ub, ldu, Vb, ldv)
+                        t["U_blocks"].append(Ub)
+                        t["V_blocks"].append(Vb)
+                tasks.append(t)
         sets.append(tasks)
     return sets
 
@@ -166,14 +175,16 @@ def cpu_baseline_configs(inputs):
 class Leg:
     """One timed configuration of the whole iteration (factor dtype, streams, step dependency)."""
 
-    def __init__(self, layers, fc_dtype_name, psd, inputs, torch, dev, n_sets, rule, one_stream=False):
+    def __init__(self, layers, fc_dtype_name, psd, inputs, torch, dev, n_sets, rule, one_stream=False, bf16_blocks=False):
         self.layers, self.psd, self.inputs, self.torch = layers, psd, inputs, torch
         self.name = fc_dtype_name
         self.rule = rule
         fc_dtype = psd.BF16 if fc_dtype_name == "bf16" else psd.F32
-        self.sets = build_device_sets(layers, fc_dtype, n_sets, psd, torch, dev, one_stream)
+        self.sets = build_device_sets(layers, fc_dtype, n_sets, psd, torch, dev, one_stream, bf16_blocks)
         self.n_sets = n_sets
-        self.blocks_in_place = False     # fp32 only: FC layers handed over without stacked buffers (no pack launch)
+        # FC layers handed over without stacked buffers (no pack launch): fp32 blocks as they are, or (sets built
+        # with bf16_blocks) bf16 blocks as senders that round before sending deliver them
+        self.blocks_in_place = False
         self.work = [layer_work(L, fc_dtype_name) for L in layers]
         self.kinds = [psd.LAYER_CONV if L["kind"] == "conv" else psd.LAYER_FC for L in layers]
         self.dims = [(L["n"], 1) if L["kind"] == "conv" else (L["M"], L["N"]) for L in layers]
@@ -203,8 +214,12 @@ class Leg:
             tasks = [dict(t) for t in self.sets[i % self.n_sets]]
             if self.blocks_in_place:
                 for t in tasks:
-                    if t["kind"] == "fc" and t["factor_dtype"] == psd.F32 and psd.sfb_blocks_supported(t["plan"]):
-                        t.update(U=None, V=None)
+                    if t["kind"] != "fc":
+                        continue
+                    if t["factor_dtype"] == psd.F32 and psd.sfb_blocks_supported(t["plan"]):
+                        t.update(U=None, V=None, ldu=0, ldv=0)
+                    elif "U_blocks" in t and psd.sfb_blocks_supported(t["plan"], psd.BF16, t["ldu"], t["ldv"]):
+                        t.update(U=None, V=None, delta_f32=t["delta"], act_f32=t["act"], delta=t["U_blocks"], act=t["V_blocks"])
             if dependent:
                 for t in tasks:
                     t["ev_ready"] = self.ev_step_done   # "the iteration before has finished on every stream"
@@ -216,8 +231,15 @@ class Leg:
             iters.append(psd.Iteration(tasks))
             marks.append(m)
 
+        own = [[t for t in self.sets[i % self.n_sets] if "U_blocks" in t] if self.blocks_in_place else []
+               for i in range(total)]
+
         def step(i):
             it = iters[i]
+            # bf16 blocks read in place: this worker still rounds its OWN block (1/P of the stacking pass)
+            for t in own[i]:
+                psd.pack_factors(t["one"], [t["delta"][0]], [t["act"][0]], psd.BF16, t["U_blocks"][0], t["ldu"],
+                                 t["V_blocks"][0], t["ldv"], stream=t["stream"])
             # route selection for every layer (Algorithm 3), then the top-down issue; with `dependent` every
             # layer's stream first waits for ev_step_done of the step before
             for j, (kind, (M, N)) in enumerate(zip(self.kinds, self.dims)):
@@ -444,6 +466,15 @@ def main():
         side["%s_ms_per_step" % ("eight_streams" if args.one_stream else "one_stream")] = round(ms_one, 4)
         del one
         torch.cuda.empty_cache()
+        if args.fc_dtype == "bf16":
+            # the same step when the peers' factors arrive as bf16 blocks (rounded by their senders) and are read in
+            # place: no stacking pass, only this worker's own block is rounded (psd_sync_fc_sfb_blocks)
+            inp = Leg(layers, "bf16", psd, inputs, torch, dev, args.sets, rule, args.one_stream, bf16_blocks=True)
+            inp.blocks_in_place = True
+            ms_inp, _ = inp.run(args.steps, args.warmup, dependent=False)
+            side["bf16_blocks_read_in_place_ms_per_step"] = round(ms_inp, 4)
+            del inp
+            torch.cuda.empty_cache()
         other = "f32" if args.fc_dtype == "bf16" else "bf16"
         leg2 = Leg(layers, other, psd, inputs, torch, dev, args.sets, rule, args.one_stream)
         ev2 = HipEvents()

@@ -146,18 +146,22 @@ psd_status psd_sync_fc_sfb_static(const psd_plan* plan, int32_t factor_dtype,
                                   const void* U, int64_t ldu, const void* V, int64_t ldv,
                                   float* W, float* Mom, float lr, float mu, float wd, void* stream);
 
-/* psd_sync_fc_sfb for fp32 factors WITHOUT the stacking pass: the reconstruction reads the P per-worker
- * blocks where they lie (row k = p*B + b of U is row b of delta_p[p], of V row b of act_p[p]) -- the
- * stacked matrices of SFB steps 1-2 need not exist when the factors are used as they were received.
- * Same arithmetic in the same order as psd_pack_factors (fp32) followed by psd_sync_fc_sfb without a
- * workspace: results are identical bit for bit.
- *   delta_p, act_p [host] arrays of P [dev] pointers (B x N and B x M fp32 row-major, 16-byte aligned).
- * Served when B is a multiple of 16 (a k-stage of the kernel never straddles two blocks) and N and M are
- * multiples of 4 (every row of every block starts on a 16-byte boundary); psd_sfb_blocks_supported tells.
- * Any other layer is refused with PSD_E_UNSUPPORTED before anything is launched: stack it. */
-int32_t psd_sfb_blocks_supported(const psd_plan* plan);
-psd_status psd_sync_fc_sfb_blocks(const psd_plan* plan, const float* const* delta_p, const float* const* act_p,
-                                  float* W, float* Mom, float lr, float mu, float wd, void* stream);
+/* psd_sync_fc_sfb WITHOUT the stacking pass: the reconstruction reads the P per-worker factor blocks where
+ * they lie (row k = p*B + b of U is row b of U_p[p], of V row b of V_p[p]) -- the stacked matrices of SFB
+ * steps 1-2 need not exist when the factors can be used as they were received: fp32 factors straight from
+ * backpropagation and from the peers (ldu = N, ldv = M), or bf16 factors that every sender rounded before
+ * sending (a block is then what psd_pack_factors writes for a one-worker plan).
+ * Same arithmetic in the same order as psd_sync_fc_sfb (no workspace) on the stacked matrices: results are
+ * identical bit for bit.
+ *   U_p, V_p [host] arrays of P [dev] pointers to B x ldu and B x ldv elements of factor_dtype, row-major,
+ *   16-byte aligned, read only.  ldu >= N, ldv >= M, rows a multiple of 16 bytes.
+ * Served when B is a multiple of the kernel's k-stage (16 rows for fp32, 32 for bf16: a stage never
+ * straddles two blocks); psd_sfb_blocks_supported tells (1 = yes).  Any other layer is refused with
+ * PSD_E_UNSUPPORTED before anything is launched: stack it. */
+int32_t psd_sfb_blocks_supported(const psd_plan* plan, int32_t factor_dtype, int64_t ldu, int64_t ldv);
+psd_status psd_sync_fc_sfb_blocks(const psd_plan* plan, int32_t factor_dtype, const void* const* U_p, int64_t ldu,
+                                  const void* const* V_p, int64_t ldv, float* W, float* Mom, float lr, float mu,
+                                  float wd, void* stream);
 
 /* Bias of an FC layer under SFB.  For z = W a + b the per-sample gradient w.r.t. b is the error
  * vector itself (the chain rule behind Eq. 5), so with the stacked errors U of the layer
@@ -199,11 +203,12 @@ typedef struct psd_layer_task {
     psd_plan plan;             /* from psd_plan_layer */
     int32_t factor_dtype;      /* FC: PSD_F32 or PSD_BF16 */
     int32_t S;                 /* PS route: shards */
-    const float* const* delta_p; /* FC: [host] P [dev] pointers, B x N each */
-    const float* const* act_p;   /* FC: [host] P [dev] pointers, B x M each */
+    const void* const* delta_p; /* FC: [host] P [dev] pointers, B x N fp32 each (errors) */
+    const void* const* act_p;   /* FC: [host] P [dev] pointers, B x M fp32 each (activations) */
     void* U; int64_t ldu;      /* FC: [dev] K x ldu stacked errors (written, then read) */
-    void* V; int64_t ldv;      /* FC: [dev] K x ldv stacked activations.  U == V == NULL with fp32 factors:
-                                  no stacked copy, the blocks are read in place (psd_sync_fc_sfb_blocks) */
+    void* V; int64_t ldv;      /* FC: [dev] K x ldv stacked activations.  U == V == NULL: no stacked copy;
+                                  delta_p / act_p then hold blocks of factor_dtype with leading dimensions
+                                  ldu / ldv (0 = N / M) that are read in place (psd_sync_fc_sfb_blocks) */
     const float* const* G;     /* PS route: [host] P [dev] pointers, M*N fp32 each (may be
                                   NULL for an FC layer that is routed to SFB / SF_PS) */
     float* W; float* Mom;      /* [dev] N x M fp32 */
@@ -224,7 +229,7 @@ typedef struct psd_layer_task {
  * stream as if its gradient had just been produced by backpropagation.  Each layer follows
  * the route its plan holds under `rule`: PS_DENSE -> psd_sync_dense_ps; SFB or SF_PS ->
  * psd_pack_factors then psd_sync_fc_sfb (with the layer's workspace, if any), or psd_sync_fc_sfb_blocks
- * alone for an fp32 layer given without stacked buffers.  Layers own disjoint
+ * alone for a layer given without stacked buffers.  Layers own disjoint
  * parameters (Section 4.2), so no ordering between streams is needed; the caller synchronises the
  * streams.
  * Consecutive PS_DENSE layers whose gradients become available together (none has an ev_ready, or all

@@ -86,9 +86,10 @@ SIGNATURES = {
     "psd_sync_fc_sfb_static": (ctypes.c_int32, [ctypes.POINTER(Plan), ctypes.c_int32, ctypes.c_void_p, ctypes.c_int64,
                                                 ctypes.c_void_p, ctypes.c_int64, ctypes.c_void_p, ctypes.c_void_p,
                                                 ctypes.c_float, ctypes.c_float, ctypes.c_float, ctypes.c_void_p]),
-    "psd_sfb_blocks_supported": (ctypes.c_int32, [ctypes.POINTER(Plan)]),
-    "psd_sync_fc_sfb_blocks": (ctypes.c_int32, [ctypes.POINTER(Plan), _f32pp, _f32pp, ctypes.c_void_p, ctypes.c_void_p,
-                                                ctypes.c_float, ctypes.c_float, ctypes.c_float, ctypes.c_void_p]),
+    "psd_sfb_blocks_supported": (ctypes.c_int32, [ctypes.POINTER(Plan), ctypes.c_int32, ctypes.c_int64, ctypes.c_int64]),
+    "psd_sync_fc_sfb_blocks": (ctypes.c_int32, [ctypes.POINTER(Plan), ctypes.c_int32, _f32pp, ctypes.c_int64, _f32pp,
+                                                ctypes.c_int64, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_float,
+                                                ctypes.c_float, ctypes.c_float, ctypes.c_void_p]),
     "psd_sync_fc_bias": (ctypes.c_int32, [ctypes.POINTER(Plan), ctypes.c_int32, ctypes.c_void_p, ctypes.c_int64,
                                           ctypes.c_void_p, ctypes.c_void_p, ctypes.c_float, ctypes.c_float,
                                           ctypes.c_float, ctypes.c_void_p]),
@@ -158,10 +159,10 @@ def _dev_ptr(t, dtype, min_elems, what):
     return t.data_ptr()
 
 
-def _ptr_array(tensors, min_elems, what):
+def _ptr_array(tensors, min_elems, what, dtype=torch.float32):
     arr = (_f32p * len(tensors))()
     for i, t in enumerate(tensors):
-        arr[i] = ctypes.cast(_dev_ptr(t, torch.float32, min_elems, "%s[%d]" % (what, i)), _f32p)
+        arr[i] = ctypes.cast(_dev_ptr(t, dtype, min_elems, "%s[%d]" % (what, i)), _f32p)
     return arr
 
 
@@ -251,20 +252,24 @@ def sync_fc_sfb_static(plan, factor_dtype, U, ldu, V, ldv, W, Mom, lr, mu, strea
                                         _stream_handle(stream)), "psd_sync_fc_sfb_static")
 
 
-def sfb_blocks_supported(plan):
-    return bool(lib().psd_sfb_blocks_supported(ctypes.byref(plan)))
+def sfb_blocks_supported(plan, factor_dtype=F32, ldu=0, ldv=0):
+    """ldu / ldv = 0: dense blocks (rows of N and M elements)."""
+    return bool(lib().psd_sfb_blocks_supported(ctypes.byref(plan), factor_dtype, ldu or plan.N, ldv or plan.M))
 
 
-def sync_fc_sfb_blocks(plan, delta, act, W, Mom, lr, mu, stream=None, wd=0.0):
-    """fp32 reconstruction + update straight from the P per-worker blocks (no stacked copy)."""
-    if len(delta) != plan.P or len(act) != plan.P:
+def sync_fc_sfb_blocks(plan, factor_dtype, U_blocks, ldu, V_blocks, ldv, W, Mom, lr, mu, stream=None, wd=0.0):
+    """Reconstruction + update straight from the P per-worker blocks (B x ldu and B x ldv elements of
+    factor_dtype each), no stacked copy.  ldu / ldv = 0: dense blocks."""
+    if len(U_blocks) != plan.P or len(V_blocks) != plan.P:
         raise ValueError("need P per-worker blocks")
-    d = _ptr_array(delta, plan.B * plan.N, "delta")
-    a = _ptr_array(act, plan.B * plan.M, "act")
+    ldu, ldv = ldu or plan.N, ldv or plan.M
+    fd = _FACTOR_TORCH.get(factor_dtype, ())
+    d = _ptr_array(U_blocks, plan.B * ldu, "U_blocks", fd)
+    a = _ptr_array(V_blocks, plan.B * ldv, "V_blocks", fd)
     wp = _dev_ptr(W, torch.float32, plan.N * plan.M, "W")
     mp = _dev_ptr(Mom, torch.float32, plan.N * plan.M, "Mom")
-    _check(lib().psd_sync_fc_sfb_blocks(ctypes.byref(plan), d, a, wp, mp, lr, mu, wd, _stream_handle(stream)),
-           "psd_sync_fc_sfb_blocks")
+    _check(lib().psd_sync_fc_sfb_blocks(ctypes.byref(plan), factor_dtype, d, ldu, a, ldv, wp, mp, lr, mu, wd,
+                                        _stream_handle(stream)), "psd_sync_fc_sfb_blocks")
 
 
 def sync_fc_bias(plan, factor_dtype, U, ldu, bias, mom_bias, lr, mu, stream=None, wd=0.0):
@@ -375,7 +380,8 @@ class Iteration:
     """Marshalled, reusable argument block for psd_sync_iteration (layers bottom-up).
 
     Each layer is a dict: FC  -> plan, factor_dtype, delta, act, U, ldu, V, ldv, W, Mom, stream[, workspace]
-                                 (U = V = None with fp32 factors: the blocks are read in place, nothing is stacked)
+                                 (U = V = None: delta / act are blocks of factor_dtype with leading dimensions
+                                 ldu / ldv (0 or absent = dense) that are read in place, nothing is stacked)
                          conv -> plan, G, S, W, Mom, stream
     plus optional ev_ready (the layer's stream waits for it first) and ev_begin / ev_end (recorded
     around the layer's sync kernel); all raw hipEvent_t handles as ints.
@@ -404,14 +410,19 @@ class Iteration:
                 self._keep.append(g)
                 t.G = ctypes.cast(g, _f32pp)
             if L.get("delta") is not None:
-                d = _ptr_array(L["delta"], plan.B * plan.N, "delta")
-                a = _ptr_array(L["act"], plan.B * plan.M, "act")
-                self._keep += [d, a]
-                t.delta_p, t.act_p = ctypes.cast(d, _f32pp), ctypes.cast(a, _f32pp)
                 fd = _FACTOR_TORCH.get(t.factor_dtype, ())
-                if L.get("U") is not None or L.get("V") is not None:      # neither: fp32 blocks read in place
+                if L.get("U") is not None or L.get("V") is not None:
+                    d = _ptr_array(L["delta"], plan.B * plan.N, "delta")
+                    a = _ptr_array(L["act"], plan.B * plan.M, "act")
                     t.U, t.ldu = _dev_ptr(L["U"], fd, plan.K * L["ldu"], "U"), L["ldu"]
                     t.V, t.ldv = _dev_ptr(L["V"], fd, plan.K * L["ldv"], "V"), L["ldv"]
+                else:
+                    # no stacked buffers: delta / act are blocks of factor_dtype, read in place
+                    t.ldu, t.ldv = L.get("ldu") or plan.N, L.get("ldv") or plan.M
+                    d = _ptr_array(L["delta"], plan.B * t.ldu, "delta", fd)
+                    a = _ptr_array(L["act"], plan.B * t.ldv, "act", fd)
+                self._keep += [d, a]
+                t.delta_p, t.act_p = ctypes.cast(d, _f32pp), ctypes.cast(a, _f32pp)
         self.L = len(layers)
 
     def run(self, lr, mu, rule=RULE_ALG3, wd=0.0):

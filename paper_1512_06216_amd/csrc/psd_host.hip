@@ -194,25 +194,37 @@ psd_status psd_sync_fc_sfb(const psd_plan* plan, int32_t factor_dtype, const voi
                            plan->N, plan->M, K, lr, mu, wd, part, splits, st);
 }
 
-int32_t psd_sfb_blocks_supported(const psd_plan* plan)
+int32_t psd_sfb_blocks_supported(const psd_plan* plan, int32_t factor_dtype, int64_t ldu, int64_t ldv)
 {
-    return plan && valid_plan_sizes(plan) && sfb_f32_blocks_supported(plan->N, plan->M, plan->B) ? 1 : 0;
+    if (!plan || !valid_plan_sizes(plan) || (factor_dtype != PSD_F32 && factor_dtype != PSD_BF16)) return 0;
+    if (!valid_ld(ldu, plan->N, factor_dtype) || !valid_ld(ldv, plan->M, factor_dtype)) return 0;
+    return (factor_dtype == PSD_F32 ? sfb_f32_blocks_supported(plan->B) : sfb_bf16_blocks_supported(plan->B)) ? 1 : 0;
 }
 
-psd_status psd_sync_fc_sfb_blocks(const psd_plan* plan, const float* const* delta_p, const float* const* act_p,
-                                  float* W, float* Mom, float lr, float mu, float wd, void* stream)
+psd_status psd_sync_fc_sfb_blocks(const psd_plan* plan, int32_t factor_dtype, const void* const* U_p, int64_t ldu,
+                                  const void* const* V_p, int64_t ldv, float* W, float* Mom, float lr, float mu,
+                                  float wd, void* stream)
 {
-    if (!plan || !delta_p || !act_p || !W || !Mom) return PSD_E_NULL;
+    if (!plan || !U_p || !V_p || !W || !Mom) return PSD_E_NULL;
+    if (factor_dtype != PSD_F32 && factor_dtype != PSD_BF16) return PSD_E_INVALID;
     if (!(wd >= 0.0f)) return PSD_E_INVALID;          // also rejects NaN
     if (!valid_plan_sizes(plan)) return PSD_E_INVALID;
     if (!aligned16(W) || !aligned16(Mom) || W == Mom) return PSD_E_INVALID;
     for (int64_t p = 0; p < plan->P; ++p) {
-        if (!delta_p[p] || !act_p[p]) return PSD_E_NULL;
-        if (!aligned16(delta_p[p]) || !aligned16(act_p[p])) return PSD_E_INVALID;
+        if (!U_p[p] || !V_p[p]) return PSD_E_NULL;
+        if (!aligned16(U_p[p]) || !aligned16(V_p[p])) return PSD_E_INVALID;
     }
-    if (!sfb_f32_blocks_supported(plan->N, plan->M, plan->B)) return PSD_E_UNSUPPORTED;
-    return launch_sfb_f32_blocks(delta_p, act_p, plan->P, plan->B, W, Mom, plan->N, plan->M, lr, mu, wd,
-                                 static_cast<hipStream_t>(stream));
+    // rows that are not a multiple of 16 bytes (or shorter than the layer is wide), or blocks that do not hold
+    // whole k-stages: this layer has to be stacked
+    if (!psd_sfb_blocks_supported(plan, factor_dtype, ldu, ldv)) return PSD_E_UNSUPPORTED;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    if (factor_dtype == PSD_F32)
+        return launch_sfb_f32_blocks(reinterpret_cast<const float* const*>(U_p), ldu,
+                                     reinterpret_cast<const float* const*>(V_p), ldv, plan->P, plan->B, W, Mom, plan->N,
+                                     plan->M, lr, mu, wd, st);
+    return launch_sfb_bf16_blocks(reinterpret_cast<const uint16_t* const*>(U_p), ldu,
+                                  reinterpret_cast<const uint16_t* const*>(V_p), ldv, plan->P, plan->B, W, Mom, plan->N,
+                                  plan->M, lr, mu, wd, st);
 }
 
 psd_status psd_sync_fc_bias(const psd_plan* plan, int32_t factor_dtype, const void* U, int64_t ldu, float* bias,
@@ -379,12 +391,15 @@ psd_status psd_sync_iteration(int32_t L, const psd_layer_task* layers, float lr,
                                   lr, mu, wd, t.S, t.stream);
         } else if (route == PSD_ROUTE_SFB || route == PSD_ROUTE_SF_PS) {
             if (t.plan.kind != PSD_LAYER_FC) return PSD_E_INVALID;
-            if (!t.U && !t.V && t.factor_dtype == PSD_F32) {
-                // no stacked buffers given: the fp32 blocks are read where they lie
+            if (!t.U && !t.V) {
+                // no stacked buffers given: delta_p / act_p hold blocks of factor_dtype, read where they lie
                 if (t.ev_begin) PSD_HIP_TRY(hipEventRecord(static_cast<hipEvent_t>(t.ev_begin), st));
-                r = psd_sync_fc_sfb_blocks(&t.plan, t.delta_p, t.act_p, t.W, t.Mom, lr, mu, wd, t.stream);
+                r = psd_sync_fc_sfb_blocks(&t.plan, t.factor_dtype, t.delta_p, t.ldu ? t.ldu : t.plan.N, t.act_p,
+                                           t.ldv ? t.ldv : t.plan.M, t.W, t.Mom, lr, mu, wd, t.stream);
             } else {
-                r = psd_pack_factors(&t.plan, t.delta_p, t.act_p, t.factor_dtype, t.U, t.ldu, t.V, t.ldv, t.stream);
+                r = psd_pack_factors(&t.plan, static_cast<const float* const*>(static_cast<const void*>(t.delta_p)),
+                                     static_cast<const float* const*>(static_cast<const void*>(t.act_p)), t.factor_dtype,
+                                     t.U, t.ldu, t.V, t.ldv, t.stream);
                 if (r == PSD_OK && t.ev_begin) PSD_HIP_TRY(hipEventRecord(static_cast<hipEvent_t>(t.ev_begin), st));
                 if (r == PSD_OK)
                     r = psd_sync_fc_sfb(&t.plan, t.factor_dtype, t.U, t.ldu, t.V, t.ldv, t.W, t.Mom, lr, mu, wd,

@@ -74,11 +74,16 @@ psd_status launch_sfb_f32(const float* U, int64_t ldu, const float* V, int64_t l
 psd_status launch_sfb_bf16(const uint16_t* U, int64_t ldu, const uint16_t* V, int64_t ldv, float* W, float* Mom,
                            int64_t N, int64_t M, int64_t K, float lr, float mu, float wd, float* part, int splits,
                            hipStream_t st);
-// fp32 reconstruction straight from the P per-worker blocks (no stacked copy); supported when a block holds
-// whole k-stages and every row of every block is 16-byte aligned
-bool sfb_f32_blocks_supported(int64_t N, int64_t M, int64_t B);
-psd_status launch_sfb_f32_blocks(const float* const* delta_p, const float* const* act_p, int64_t P, int64_t B,
-                                 float* W, float* Mom, int64_t N, int64_t M, float lr, float mu, float wd, hipStream_t st);
+// reconstruction straight from the P per-worker blocks (B x ld each, no stacked copy); served when a block
+// holds whole k-stages of the kernel (16 rows fp32, 32 rows bf16)
+bool sfb_f32_blocks_supported(int64_t B);
+bool sfb_bf16_blocks_supported(int64_t B);
+psd_status launch_sfb_f32_blocks(const float* const* U_p, int64_t ldu, const float* const* V_p, int64_t ldv, int64_t P,
+                                 int64_t B, float* W, float* Mom, int64_t N, int64_t M, float lr, float mu, float wd,
+                                 hipStream_t st);
+psd_status launch_sfb_bf16_blocks(const uint16_t* const* U_p, int64_t ldu, const uint16_t* const* V_p, int64_t ldv,
+                                  int64_t P, int64_t B, float* W, float* Mom, int64_t N, int64_t M, float lr, float mu,
+                                  float wd, hipStream_t st);
 // how many ways each kernel would split K for this layer when it is given a workspace (1 = not at all)
 int sfb_f32_splits(int64_t N, int64_t M, int64_t K);
 int sfb_bf16_splits(int64_t N, int64_t M, int64_t K);

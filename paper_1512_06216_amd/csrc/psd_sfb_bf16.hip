@@ -64,13 +64,30 @@ __device__ __forceinline__ bf16x4 read_tr(uint32_t lds_addr)
 // tile, workgroup (tile, s) contracts over k-stages [s * stages_per_split, (s+1) * stages_per_split)
 // and stores its partial dW tile to part + s * part_stride (N x M row-major); the partials are summed
 // in split order and the update applied by the parameter-server sum kernel afterwards.
-template <class C, bool PART>
-__global__ void __launch_bounds__(C::THREADS, C::OCC)
-sfb_bf16_kernel(const uint16_t* __restrict__ U, int64_t ldu, const uint16_t* __restrict__ V, int64_t ldv,
-                float* __restrict__ W, float* __restrict__ Mom, int N, int M, int K, float lr, float mu, float wd,
-                int tiles_n, int tiles_m, uint32_t u_bytes, uint32_t v_bytes, float* __restrict__ part,
-                int64_t part_stride, int stages_per_split, int skew_blocks, int skew_ticks)
+// BLK = true: the factors are not stacked.  Row k = p*B + b of U is row b of the p-th worker's B x ldu block
+// (V likewise), read where it lies: a stage of KT rows never straddles two blocks because KT divides B, so
+// the only difference is that the buffer descriptors are re-aimed whenever the stages move on to the next
+// block (and aimed at nothing past the last one, which reads as zeros like the K tail does).
+struct BlockPtrs { const uint16_t* u[PSD_MAX_WORKERS]; const uint16_t* v[PSD_MAX_WORKERS]; };
+
+// a pointer every lane holds alike, moved to scalar registers (buffer descriptors live there)
+__device__ __forceinline__ const uint16_t* uniform_ptr(const uint16_t* p)
 {
+    const uint64_t a = reinterpret_cast<uint64_t>(p);
+    const uint32_t lo = __builtin_amdgcn_readfirstlane(static_cast<uint32_t>(a));
+    const uint32_t hi = __builtin_amdgcn_readfirstlane(static_cast<uint32_t>(a >> 32));
+    return reinterpret_cast<const uint16_t*>((static_cast<uint64_t>(hi) << 32) | lo);
+}
+
+template <class C, bool PART, bool BLK>
+__device__ __forceinline__ void
+sfb_bf16_body(const uint16_t* __restrict__ U, int64_t ldu, const uint16_t* __restrict__ V, int64_t ldv,
+              float* __restrict__ W, float* __restrict__ Mom, int N, int M, int K, float lr, float mu, float wd,
+              int tiles_n, int tiles_m, uint32_t u_bytes, uint32_t v_bytes, float* __restrict__ part,
+              int64_t part_stride, int stages_per_split, int skew_blocks, int skew_ticks,
+              const BlockPtrs* blocks, int n_blocks, int stages_per_block)
+{
+    static_assert(!(PART && BLK), "blocks read in place are not combined with a split of K");
     // Measurement aid (off unless asked for): the workgroups that start first on the odd-numbered
     // XCDs wait skew_ticks of the 100 MHz wall clock, which puts the two halves of the chip out of
     // phase (MFMA loop on one, W / Mom update on the other).  The wait ends by the clock; the
@@ -113,7 +130,15 @@ sfb_bf16_kernel(const uint16_t* __restrict__ U, int64_t ldu, const uint16_t* __r
         u_bytes = __builtin_amdgcn_readfirstlane(static_cast<uint32_t>(int64_t(k_end) * ldu * 2));
         v_bytes = __builtin_amdgcn_readfirstlane(static_cast<uint32_t>(int64_t(k_end) * ldv * 2));
     }
-    const i32x4 rsrc_u = raw_rsrc(U, u_bytes), rsrc_v = raw_rsrc(V, v_bytes);
+    i32x4 rsrc_u = raw_rsrc(U, u_bytes), rsrc_v = raw_rsrc(V, v_bytes);
+    int blk = 0, stage_in_blk = 0;               // BLK: where the next stage to be requested lies
+    auto aim_block = [&]() {                     // BLK: descriptors over block `blk` (u_bytes, v_bytes = one block)
+        const bool live = blk < n_blocks;
+        const int i = live ? blk : 0;            // the table is never indexed past its end
+        rsrc_u = raw_rsrc(uniform_ptr(blocks->u[i]), live ? u_bytes : 0u);
+        rsrc_v = raw_rsrc(uniform_ptr(blocks->v[i]), live ? v_bytes : 0u);
+    };
+    if constexpr (BLK) aim_block();
     uint32_t voff_a[C::NI_A], voff_b[C::NI_B];
     {
         constexpr int LPR = C::RA / 16;              // 16-byte chunks per row
@@ -136,15 +161,22 @@ sfb_bf16_kernel(const uint16_t* __restrict__ U, int64_t ldu, const uint16_t* __r
         }
     }
     const uint32_t step_a = static_cast<uint32_t>(KT * ldu * 2), step_b = static_cast<uint32_t>(KT * ldv * 2);
-    auto issue = [&](int t) {                    // stage t -> ring buffer t % NSTAGE
+    auto issue = [&](int t) {                    // stage t -> ring buffer t % NSTAGE (stages are requested in order)
         const uint32_t base = lds0 + static_cast<uint32_t>(t % C::NSTAGE) * C::STAGE_BYTES;
+        const uint32_t s = static_cast<uint32_t>(BLK ? stage_in_blk : t);
 #pragma unroll
         for (int j = 0; j < C::NI_A; ++j)
-            dma_b128(base + (wave * C::NI_A + j) * 1024, voff_a[j] + static_cast<uint32_t>(t) * step_a, rsrc_u);
+            dma_b128(base + (wave * C::NI_A + j) * 1024, voff_a[j] + s * step_a, rsrc_u);
 #pragma unroll
         for (int j = 0; j < C::NI_B; ++j)
-            dma_b128(base + C::A_BYTES + (wave * C::NI_B + j) * 1024,
-                     voff_b[j] + static_cast<uint32_t>(t) * step_b, rsrc_v);
+            dma_b128(base + C::A_BYTES + (wave * C::NI_B + j) * 1024, voff_b[j] + s * step_b, rsrc_v);
+        if constexpr (BLK) {
+            if (++stage_in_blk == stages_per_block) {
+                stage_in_blk = 0;
+                ++blk;
+                aim_block();
+            }
+        }
     };
 
     // ---- transposing-read plan.  A 16-lane group reads a (4 k) x (16 column) patch: lane L
@@ -320,6 +352,51 @@ sfb_bf16_kernel(const uint16_t* __restrict__ U, int64_t ldu, const uint16_t* __r
     }
 }
 
+template <class C, bool PART>
+__global__ void __launch_bounds__(C::THREADS, C::OCC)
+sfb_bf16_kernel(const uint16_t* __restrict__ U, int64_t ldu, const uint16_t* __restrict__ V, int64_t ldv,
+                float* __restrict__ W, float* __restrict__ Mom, int N, int M, int K, float lr, float mu, float wd,
+                int tiles_n, int tiles_m, uint32_t u_bytes, uint32_t v_bytes, float* __restrict__ part,
+                int64_t part_stride, int stages_per_split, int skew_blocks, int skew_ticks)
+{
+    sfb_bf16_body<C, PART, false>(U, ldu, V, ldv, W, Mom, N, M, K, lr, mu, wd, tiles_n, tiles_m, u_bytes, v_bytes, part,
+                                  part_stride, stages_per_split, skew_blocks, skew_ticks, nullptr, 0, 0);
+}
+
+// the P per-worker blocks read in place (u_bytes, v_bytes: the size of ONE block)
+template <class C>
+__global__ void __launch_bounds__(C::THREADS, C::OCC)
+sfb_bf16_blocks_kernel(BlockPtrs blocks, int n_blocks, int stages_per_block, int64_t ldu, int64_t ldv,
+                       float* __restrict__ W, float* __restrict__ Mom, int N, int M, int K, float lr, float mu, float wd,
+                       int tiles_n, int tiles_m, uint32_t u_bytes, uint32_t v_bytes)
+{
+    sfb_bf16_body<C, false, true>(nullptr, ldu, nullptr, ldv, W, Mom, N, M, K, lr, mu, wd, tiles_n, tiles_m, u_bytes,
+                                  v_bytes, nullptr, 0, 0, 0, 0, &blocks, n_blocks, stages_per_block);
+}
+
+template <class C>
+psd_status launch_cfg_blocks(const BlockPtrs& blocks, int64_t P, int64_t B, int64_t ldu, int64_t ldv, float* W, float* Mom,
+                             int64_t N, int64_t M, float lr, float mu, float wd, hipStream_t st)
+{
+    const int64_t tiles_n = (N + C::TN - 1) / C::TN, tiles_m = (M + C::TM - 1) / C::TM;
+    const int64_t tiles = tiles_n * tiles_m;
+    if (tiles < 1 || tiles > 0x3fffffff) return PSD_E_INVALID;
+    const int64_t u_bytes = B * ldu * 2, v_bytes = B * ldv * 2;          // one block
+    if (u_bytes >= (int64_t(1) << 32) || v_bytes >= (int64_t(1) << 32)) return PSD_E_UNSUPPORTED;
+    static std::atomic<bool> attr_done{false};
+    if (!attr_done.load(std::memory_order_acquire)) {
+        PSD_HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(sfb_bf16_blocks_kernel<C>),
+                                        hipFuncAttributeMaxDynamicSharedMemorySize, int(C::LDS_BYTES)));
+        attr_done.store(true, std::memory_order_release);
+    }
+    hipLaunchKernelGGL(sfb_bf16_blocks_kernel<C>, dim3(static_cast<uint32_t>(tiles)), dim3(C::THREADS), C::LDS_BYTES, st,
+                       blocks, static_cast<int>(P), static_cast<int>(B / KT), ldu, ldv, W, Mom, static_cast<int>(N),
+                       static_cast<int>(M), static_cast<int>(P * B), lr, mu, wd, static_cast<int>(tiles_n),
+                       static_cast<int>(tiles_m), static_cast<uint32_t>(u_bytes), static_cast<uint32_t>(v_bytes));
+    PSD_HIP_TRY(hipGetLastError());
+    return PSD_OK;
+}
+
 template <class C>
 psd_status launch_cfg(const uint16_t* U, int64_t ldu, const uint16_t* V, int64_t ldv, float* W, float* Mom,
                       int64_t N, int64_t M, int64_t K, float lr, float mu, float wd, float* part, int splits,
@@ -407,6 +484,28 @@ psd_status launch_sfb_bf16(const uint16_t* U, int64_t ldu, const uint16_t* V, in
         case 0: return launch_cfg<Cfg128x256w4>(U, ldu, V, ldv, W, Mom, N, M, K, lr, mu, wd, part, splits, st);
         case 1: return launch_cfg<Cfg128x192w4>(U, ldu, V, ldv, W, Mom, N, M, K, lr, mu, wd, part, splits, st);
         default: return launch_cfg<Cfg128x128w4>(U, ldu, V, ldv, W, Mom, N, M, K, lr, mu, wd, part, splits, st);
+    }
+}
+
+bool sfb_bf16_blocks_supported(int64_t B) { return B % KT == 0; }
+
+psd_status launch_sfb_bf16_blocks(const uint16_t* const* U_p, int64_t ldu, const uint16_t* const* V_p, int64_t ldv,
+                                  int64_t P, int64_t B, float* W, float* Mom, int64_t N, int64_t M, float lr, float mu,
+                                  float wd, hipStream_t st)
+{
+    if (P < 1 || P > PSD_MAX_WORKERS || !sfb_bf16_blocks_supported(B)) return PSD_E_UNSUPPORTED;
+    BlockPtrs blocks;
+    for (int64_t p = 0; p < PSD_MAX_WORKERS; ++p) {
+        blocks.u[p] = p < P ? U_p[p] : nullptr;
+        blocks.v[p] = p < P ? V_p[p] : nullptr;
+    }
+    Bf16Tile t;
+    int unused;
+    choose_bf16(N, M, P * B, false, &t, &unused);
+    switch (t.id) {
+        case 0: return launch_cfg_blocks<Cfg128x256w4>(blocks, P, B, ldu, ldv, W, Mom, N, M, lr, mu, wd, st);
+        case 1: return launch_cfg_blocks<Cfg128x192w4>(blocks, P, B, ldu, ldv, W, Mom, N, M, lr, mu, wd, st);
+        default: return launch_cfg_blocks<Cfg128x128w4>(blocks, P, B, ldu, ldv, W, Mom, N, M, lr, mu, wd, st);
     }
 }
 

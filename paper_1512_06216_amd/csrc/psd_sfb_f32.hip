@@ -249,11 +249,11 @@ sfb_f32_kernel(const float* __restrict__ U, int64_t ldu, const float* __restrict
 // the P per-worker blocks read in place (u_bytes, v_bytes: the size of ONE block)
 template <int BN>
 __global__ void __launch_bounds__(THREADS)
-sfb_f32_blocks_kernel(BlockPtrs blocks, int n_blocks, int stages_per_block, float* __restrict__ W,
-                      float* __restrict__ Mom, int N, int M, int K, float lr, float mu, float wd, int tiles_m,
-                      int tiles, uint32_t u_bytes, uint32_t v_bytes)
+sfb_f32_blocks_kernel(BlockPtrs blocks, int n_blocks, int stages_per_block, int64_t ldu, int64_t ldv,
+                      float* __restrict__ W, float* __restrict__ Mom, int N, int M, int K, float lr, float mu, float wd,
+                      int tiles_m, int tiles, uint32_t u_bytes, uint32_t v_bytes)
 {
-    sfb_f32_body<BN, false, true>(nullptr, N, nullptr, M, W, Mom, N, M, K, lr, mu, wd, tiles_m, tiles, u_bytes, v_bytes,
+    sfb_f32_body<BN, false, true>(nullptr, ldu, nullptr, ldv, W, Mom, N, M, K, lr, mu, wd, tiles_m, tiles, u_bytes, v_bytes,
                                   nullptr, 0, 0, &blocks, n_blocks, stages_per_block);
 }
 
@@ -283,18 +283,18 @@ psd_status launch_f32(const float* U, int64_t ldu, const float* V, int64_t ldv, 
 }
 
 template <int BN>
-psd_status launch_f32_blocks(const BlockPtrs& blocks, int64_t P, int64_t B, float* W, float* Mom, int64_t N, int64_t M,
-                             float lr, float mu, float wd, hipStream_t st)
+psd_status launch_f32_blocks(const BlockPtrs& blocks, int64_t P, int64_t B, int64_t ldu, int64_t ldv, float* W,
+                             float* Mom, int64_t N, int64_t M, float lr, float mu, float wd, hipStream_t st)
 {
     constexpr int TN = 64 * BN;
     const int64_t tiles_n = (N + TN - 1) / TN, tiles_m = (M + TM - 1) / TM;
     const int64_t tiles = tiles_n * tiles_m;
     if (tiles < 1 || tiles > 0x7fffffff) return PSD_E_INVALID;
-    const int64_t u_bytes = B * N * 4, v_bytes = B * M * 4;            // one block
+    const int64_t u_bytes = B * ldu * 4, v_bytes = B * ldv * 4;        // one block
     if (u_bytes >= (int64_t(1) << 32) || v_bytes >= (int64_t(1) << 32)) return PSD_E_UNSUPPORTED;
     hipLaunchKernelGGL(sfb_f32_blocks_kernel<BN>, dim3(static_cast<uint32_t>(tiles)), dim3(THREADS), 0, st, blocks,
-                       static_cast<int>(P), static_cast<int>(B / KT), W, Mom, static_cast<int>(N), static_cast<int>(M),
-                       static_cast<int>(P * B), lr, mu, wd, static_cast<int>(tiles_m), static_cast<int>(tiles),
+                       static_cast<int>(P), static_cast<int>(B / KT), ldu, ldv, W, Mom, static_cast<int>(N),
+                       static_cast<int>(M), static_cast<int>(P * B), lr, mu, wd, static_cast<int>(tiles_m), static_cast<int>(tiles),
                        static_cast<uint32_t>(u_bytes), static_cast<uint32_t>(v_bytes));
     PSD_HIP_TRY(hipGetLastError());
     return PSD_OK;
@@ -335,25 +335,22 @@ psd_status launch_sfb_f32(const float* U, int64_t ldu, const float* V, int64_t l
     return launch_f32<2>(U, ldu, V, ldv, W, Mom, N, M, K, lr, mu, wd, part, splits, st);
 }
 
-bool sfb_f32_blocks_supported(int64_t N, int64_t M, int64_t B)
-{
-    // whole stages per block, and every row of every block starts on a 16-byte boundary
-    return B % KT == 0 && N % 4 == 0 && M % 4 == 0;
-}
+bool sfb_f32_blocks_supported(int64_t B) { return B % KT == 0; }     // whole k-stages per block
 
-psd_status launch_sfb_f32_blocks(const float* const* delta_p, const float* const* act_p, int64_t P, int64_t B,
-                                 float* W, float* Mom, int64_t N, int64_t M, float lr, float mu, float wd, hipStream_t st)
+psd_status launch_sfb_f32_blocks(const float* const* U_p, int64_t ldu, const float* const* V_p, int64_t ldv, int64_t P,
+                                 int64_t B, float* W, float* Mom, int64_t N, int64_t M, float lr, float mu, float wd,
+                                 hipStream_t st)
 {
-    if (P < 1 || P > PSD_MAX_WORKERS || !sfb_f32_blocks_supported(N, M, B)) return PSD_E_UNSUPPORTED;
+    if (P < 1 || P > PSD_MAX_WORKERS || !sfb_f32_blocks_supported(B)) return PSD_E_UNSUPPORTED;
     BlockPtrs blocks;
     for (int64_t p = 0; p < PSD_MAX_WORKERS; ++p) {
-        blocks.u[p] = p < P ? delta_p[p] : nullptr;
-        blocks.v[p] = p < P ? act_p[p] : nullptr;
+        blocks.u[p] = p < P ? U_p[p] : nullptr;
+        blocks.v[p] = p < P ? V_p[p] : nullptr;
     }
     int bn, s;
     choose_f32(N, M, P * B, false, &bn, &s);
-    if (bn == 1) return launch_f32_blocks<1>(blocks, P, B, W, Mom, N, M, lr, mu, wd, st);
-    return launch_f32_blocks<2>(blocks, P, B, W, Mom, N, M, lr, mu, wd, st);
+    if (bn == 1) return launch_f32_blocks<1>(blocks, P, B, ldu, ldv, W, Mom, N, M, lr, mu, wd, st);
+    return launch_f32_blocks<2>(blocks, P, B, ldu, ldv, W, Mom, N, M, lr, mu, wd, st);
 }
 
 }  // namespace psd

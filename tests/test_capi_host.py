@@ -267,28 +267,39 @@ def test_ssp_clock_bookkeeping_against_a_literal_ring():
 
 
 def test_blocks_in_place_support_rule_and_argument_checks():
-    """Which layers the fp32 reconstruction can read straight from the per-worker blocks, and what the entry
+    """Which layers the reconstruction can read straight from the per-worker blocks, and what the entry
     point says about bad arguments -- all decided on the host before anything is launched."""
     L = psd.lib()
-    for (M, N, B, P), ok in (((4096, 1000, 256, 8), True), ((9216, 4096, 16, 64), True), ((256, 128, 11, 4), False),
-                             ((256, 130, 16, 4), False), ((4096, 21841, 256, 8), False), ((258, 128, 32, 4), False)):
+    sup = lambda plan, dt, ldu, ldv: bool(L.psd_sfb_blocks_supported(ctypes.byref(plan), dt, ldu, ldv))
+    for (M, N, B, P, dt, ldu, ldv), ok in (
+            ((4096, 1000, 256, 8, psd.F32, 1000, 4096), True), ((9216, 4096, 16, 64, psd.F32, 4096, 9216), True),
+            ((9216, 4096, 16, 8, psd.BF16, 4096, 9216), False),       # bf16 k-stages are 32 rows
+            ((9216, 4096, 32, 8, psd.BF16, 4096, 9216), True),
+            ((4096, 21841, 256, 8, psd.BF16, 21888, 4096), True),     # padded rows of an odd-width layer
+            ((4096, 21841, 256, 8, psd.BF16, 21841, 4096), False),    # rows not a multiple of 16 bytes
+            ((256, 128, 11, 4, psd.F32, 128, 256), False),            # a stage would straddle two blocks
+            ((256, 130, 16, 4, psd.F32, 130, 256), False), ((256, 130, 16, 4, psd.F32, 132, 256), True),
+            ((256, 128, 16, 4, psd.F32, 124, 256), False)):           # rows shorter than the layer is wide
         plan = psd.plan_layer(psd.LAYER_FC, M, N, B, P)
-        assert bool(L.psd_sfb_blocks_supported(ctypes.byref(plan))) == ok
-    assert L.psd_sfb_blocks_supported(None) == 0
-    plan = psd.plan_layer(psd.LAYER_FC, 256, 130, 16, 2)           # unsupported shape: nothing is ever launched
+        assert sup(plan, dt, ldu, ldv) == ok, (M, N, B, P, dt, ldu, ldv)
+    plan = psd.plan_layer(psd.LAYER_FC, 256, 130, 16, 2)
+    assert L.psd_sfb_blocks_supported(None, psd.F32, 132, 256) == 0 and not sup(plan, 7, 132, 256)
     fake = 0x10000000
     ptrs = (ctypes.POINTER(ctypes.c_float) * 2)(*[ctypes.cast(fake + 0x100000 * i, ctypes.POINTER(ctypes.c_float)) for i in range(2)])
     pp = ctypes.cast(ptrs, ctypes.POINTER(ctypes.POINTER(ctypes.c_float)))
-    call = lambda *a: L.psd_sync_fc_sfb_blocks(*a)
     W, Mom = ctypes.c_void_p(fake + 0x800000), ctypes.c_void_p(fake + 0x900000)
-    assert call(ctypes.byref(plan), pp, pp, W, Mom, 0.1, 0.9, 0.0, None) == psd.E_UNSUPPORTED
-    assert call(None, pp, pp, W, Mom, 0.1, 0.9, 0.0, None) == psd.E_NULL
-    assert call(ctypes.byref(plan), None, pp, W, Mom, 0.1, 0.9, 0.0, None) == psd.E_NULL
-    assert call(ctypes.byref(plan), pp, pp, None, Mom, 0.1, 0.9, 0.0, None) == psd.E_NULL
-    assert call(ctypes.byref(plan), pp, pp, W, W, 0.1, 0.9, 0.0, None) == psd.E_INVALID
-    assert call(ctypes.byref(plan), pp, pp, ctypes.c_void_p(fake + 4), Mom, 0.1, 0.9, 0.0, None) == psd.E_INVALID
-    assert call(ctypes.byref(plan), pp, pp, W, Mom, 0.1, 0.9, -1.0, None) == psd.E_INVALID
+
+    def call(plan_ref, up, vp, w, mom, wd=0.0, dt=psd.F32, ldu=130, ldv=256):    # ldu = 130: unsupported, never launched
+        return L.psd_sync_fc_sfb_blocks(plan_ref, dt, up, ldu, vp, ldv, w, mom, 0.1, 0.9, wd, None)
+    assert call(ctypes.byref(plan), pp, pp, W, Mom) == psd.E_UNSUPPORTED
+    assert call(None, pp, pp, W, Mom) == psd.E_NULL
+    assert call(ctypes.byref(plan), None, pp, W, Mom) == psd.E_NULL
+    assert call(ctypes.byref(plan), pp, pp, None, Mom) == psd.E_NULL
+    assert call(ctypes.byref(plan), pp, pp, W, W) == psd.E_INVALID
+    assert call(ctypes.byref(plan), pp, pp, ctypes.c_void_p(fake + 4), Mom) == psd.E_INVALID
+    assert call(ctypes.byref(plan), pp, pp, W, Mom, wd=-1.0) == psd.E_INVALID
+    assert call(ctypes.byref(plan), pp, pp, W, Mom, dt=5) == psd.E_INVALID
     ptrs[1] = ctypes.cast(fake + 8, ctypes.POINTER(ctypes.c_float))
-    assert call(ctypes.byref(plan), pp, pp, W, Mom, 0.1, 0.9, 0.0, None) == psd.E_INVALID
+    assert call(ctypes.byref(plan), pp, pp, W, Mom) == psd.E_INVALID
     ptrs[1] = ctypes.cast(None, ctypes.POINTER(ctypes.c_float))
-    assert call(ctypes.byref(plan), pp, pp, W, Mom, 0.1, 0.9, 0.0, None) == psd.E_NULL
+    assert call(ctypes.byref(plan), pp, pp, W, Mom) == psd.E_NULL

@@ -553,7 +553,8 @@ def test_sfb_blocks_in_place_bit_exact_and_identical_to_the_stacked_path(M, N, B
     plan = psd.plan_layer(psd.LAYER_FC, M, N, B, P)
     assert psd.sfb_blocks_supported(plan)
     W, Mom = dev(d["W"]), dev(d["Mom"])
-    psd.sync_fc_sfb_blocks(plan, [dev(x) for x in d["delta"]], [dev(x) for x in d["act"]], W, Mom, 0.25, 0.5, wd=0.5)
+    psd.sync_fc_sfb_blocks(plan, psd.F32, [dev(x) for x in d["delta"]], 0, [dev(x) for x in d["act"]], 0, W, Mom, 0.25, 0.5,
+                           wd=0.5)
     torch.cuda.synchronize()
     U, V = orc.pack_factors(d["delta"], d["act"])
     Wr, Mr = orc.sync_fc_sfb(U, V, d["W"], d["Mom"], 0.25, 0.5, wd=0.5)
@@ -562,7 +563,8 @@ def test_sfb_blocks_in_place_bit_exact_and_identical_to_the_stacked_path(M, N, B
     g = inputs.fc_layer(M=M, N=N, B=B, P=P, seed=M + 2 * P, mom_std=1e-4)
     Ws, Ms, _ = run_sfb(g, psd.F32, inputs.LR, inputs.MU)
     W, Mom = dev(g["W"]), dev(g["Mom"])
-    psd.sync_fc_sfb_blocks(plan, [dev(x) for x in g["delta"]], [dev(x) for x in g["act"]], W, Mom, inputs.LR, inputs.MU)
+    psd.sync_fc_sfb_blocks(plan, psd.F32, [dev(x) for x in g["delta"]], 0, [dev(x) for x in g["act"]], 0, W, Mom,
+                           inputs.LR, inputs.MU)
     torch.cuda.synchronize()
     assert np.array_equal(Mom.cpu().numpy(), Ms) and np.array_equal(W.cpu().numpy(), Ws)
 
@@ -572,22 +574,88 @@ def test_sfb_blocks_in_place_at_the_classifier_size():
     d = inputs.fc_config(2)
     plan = psd.plan_layer(psd.LAYER_FC, d["M"], d["N"], d["B"], d["P"])
     W, Mom = dev(d["W"]), dev(d["Mom"])
-    psd.sync_fc_sfb_blocks(plan, [dev(x) for x in d["delta"]], [dev(x) for x in d["act"]], W, Mom, inputs.LR, inputs.MU)
+    psd.sync_fc_sfb_blocks(plan, psd.F32, [dev(x) for x in d["delta"]], 0, [dev(x) for x in d["act"]], 0, W, Mom,
+                           inputs.LR, inputs.MU)
     torch.cuda.synchronize()
     _whole_matrix_checks(d, W.cpu().numpy(), Mom.cpu().numpy(), "f32", inputs.LR, inputs.MU)
 
 
-@pytest.mark.parametrize("M,N,B,P", [(256, 128, 11, 4), (256, 130, 16, 4), (21841, 64, 16, 2)])
-def test_sfb_blocks_in_place_refuses_layers_it_cannot_read(M, N, B, P):
-    # a k-stage would straddle two blocks (B), or rows of a block would not be 16-byte aligned (N, M)
+@pytest.mark.parametrize("M,N,B,P,dtype", [(256, 128, 11, 4, psd.F32), (256, 130, 16, 4, psd.F32), (21841, 64, 16, 2, psd.F32),
+                                           (256, 128, 16, 4, psd.BF16)])
+def test_sfb_blocks_in_place_refuses_layers_it_cannot_read(M, N, B, P, dtype):
+    # a k-stage would straddle two blocks (B), or rows of a dense block would not be 16-byte aligned (N, M)
     plan = psd.plan_layer(psd.LAYER_FC, M, N, B, P)
-    assert not psd.sfb_blocks_supported(plan)
+    assert not psd.sfb_blocks_supported(plan, dtype)
+    td = torch.float32 if dtype == psd.F32 else torch.bfloat16
     W, Mom = torch.zeros(N, M, device=DEV), torch.zeros(N, M, device=DEV)
-    delta = [torch.zeros(B, N, device=DEV) for _ in range(P)]
-    act = [torch.zeros(B, M, device=DEV) for _ in range(P)]
+    U_blocks = [torch.zeros(B, N, device=DEV, dtype=td) for _ in range(P)]
+    V_blocks = [torch.zeros(B, M, device=DEV, dtype=td) for _ in range(P)]
     with pytest.raises(psd.PsdError) as e:
-        psd.sync_fc_sfb_blocks(plan, delta, act, W, Mom, 0.01, 0.9)
+        psd.sync_fc_sfb_blocks(plan, dtype, U_blocks, 0, V_blocks, 0, W, Mom, 0.01, 0.9)
     assert e.value.status == psd.E_UNSUPPORTED
+
+
+BF16_BLOCK_SHAPES = [  # M, N, B, P with B a multiple of 32; odd widths get padded rows
+    (256, 128, 32, 4),
+    (700, 260, 64, 9),        # K = 576: ragged tiles both ways, two stages per block
+    (1001, 333, 32, 5),       # odd widths: blocks with padded rows (ld from psd_factor_ld), element-wise epilogue
+    (260, 204, 32, 64),       # every entry of the pointer table in use
+]
+
+
+@pytest.mark.parametrize("M,N,B,P", BF16_BLOCK_SHAPES)
+def test_sfb_bf16_blocks_in_place_bit_exact_and_identical_to_the_stacked_path(M, N, B, P):
+    """bf16 factors that arrive already rounded, one block per worker (what psd_pack_factors writes for a
+    one-worker plan), read in place: bit-exact against the oracle on integer data, and the very bits of the
+    stacked path on Gaussian data."""
+    plan = psd.plan_layer(psd.LAYER_FC, M, N, B, P)
+    one = psd.plan_layer(psd.LAYER_FC, M, N, B, 1)
+    ldu, ldv = psd.factor_ld(N, psd.BF16), psd.factor_ld(M, psd.BF16)
+    assert psd.sfb_blocks_supported(plan, psd.BF16, ldu, ldv)
+
+    def sender_side(d):            # every worker rounds its own block
+        Ub, Vb = [], []
+        for p in range(P):
+            U, _, V, _ = psd.alloc_factors(one, psd.BF16, DEV)
+            psd.pack_factors(one, [dev(d["delta"][p])], [dev(d["act"][p])], psd.BF16, U, ldu, V, ldv)
+            Ub.append(U)
+            Vb.append(V)
+        return Ub, Vb
+
+    d = inputs.fc_layer_integer(M=M, N=N, B=B, P=P, seed=M + P, amax=2 if B * P > 500 else 3)
+    Ub, Vb = sender_side(d)
+    W, Mom = dev(d["W"]), dev(d["Mom"])
+    psd.sync_fc_sfb_blocks(plan, psd.BF16, Ub, ldu, Vb, ldv, W, Mom, 0.25, 0.5, wd=0.5)
+    torch.cuda.synchronize()
+    U, V = orc.pack_factors(d["delta"], d["act"])
+    Wr, Mr = orc.sync_fc_sfb(U, V, d["W"], d["Mom"], 0.25, 0.5, wd=0.5)
+    assert np.array_equal(Mom.cpu().numpy(), Mr) and np.array_equal(W.cpu().numpy(), Wr)
+
+    g = inputs.fc_layer(M=M, N=N, B=B, P=P, seed=M + 2 * P, mom_std=1e-4)
+    Ws, Ms, _ = run_sfb(g, psd.BF16, inputs.LR, inputs.MU)
+    Ub, Vb = sender_side(g)
+    W, Mom = dev(g["W"]), dev(g["Mom"])
+    psd.sync_fc_sfb_blocks(plan, psd.BF16, Ub, ldu, Vb, ldv, W, Mom, inputs.LR, inputs.MU)
+    torch.cuda.synchronize()
+    assert np.array_equal(Mom.cpu().numpy(), Ms) and np.array_equal(W.cpu().numpy(), Ws)
+
+
+def test_sfb_bf16_blocks_in_place_at_the_fc6_size():
+    """Config 3 (9216 -> 4096, K = 2048, bf16) from eight ready-made bf16 blocks: whole matrix against the oracle."""
+    d = inputs.fc_config(3)
+    plan = psd.plan_layer(psd.LAYER_FC, d["M"], d["N"], d["B"], d["P"])
+    one = psd.plan_layer(psd.LAYER_FC, d["M"], d["N"], d["B"], 1)
+    ldu, ldv = psd.factor_ld(d["N"], psd.BF16), psd.factor_ld(d["M"], psd.BF16)
+    Ub, Vb = [], []
+    for p in range(d["P"]):
+        U, _, V, _ = psd.alloc_factors(one, psd.BF16, DEV)
+        psd.pack_factors(one, [dev(d["delta"][p])], [dev(d["act"][p])], psd.BF16, U, ldu, V, ldv)
+        Ub.append(U)
+        Vb.append(V)
+    W, Mom = dev(d["W"]), dev(d["Mom"])
+    psd.sync_fc_sfb_blocks(plan, psd.BF16, Ub, ldu, Vb, ldv, W, Mom, inputs.LR, inputs.MU)
+    torch.cuda.synchronize()
+    _whole_matrix_checks(d, W.cpu().numpy(), Mom.cpu().numpy(), "bf16", inputs.LR, inputs.MU)
 
 
 def test_iteration_reads_fp32_blocks_in_place_when_no_stacked_buffers_are_given():
