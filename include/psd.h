@@ -203,8 +203,9 @@ typedef struct psd_layer_task {
     psd_plan plan;             /* from psd_plan_layer */
     int32_t factor_dtype;      /* FC: PSD_F32 or PSD_BF16 */
     int32_t S;                 /* PS route: shards */
-    const void* const* delta_p; /* FC: [host] P [dev] pointers, B x N fp32 each (errors) */
-    const void* const* act_p;   /* FC: [host] P [dev] pointers, B x M fp32 each (activations) */
+    const void* const* delta_p; /* FC: [host] P [dev] pointers to the workers' error blocks: B x N fp32 each */
+    const void* const* act_p;   /* FC: [host] P [dev] pointers to the workers' activation blocks: B x M fp32 each
+                                   (for both: B x ldu / B x ldv elements of factor_dtype when read in place, see V) */
     void* U; int64_t ldu;      /* FC: [dev] K x ldu stacked errors (written, then read) */
     void* V; int64_t ldv;      /* FC: [dev] K x ldv stacked activations.  U == V == NULL: no stacked copy;
                                   delta_p / act_p then hold blocks of factor_dtype with leading dimensions

@@ -677,6 +677,37 @@ def test_iteration_reads_fp32_blocks_in_place_when_no_stacked_buffers_are_given(
         assert np.array_equal(w0, w1) and np.array_equal(m0, m1)
 
 
+def test_iteration_reads_bf16_blocks_in_place():
+    """Layers handed to psd_sync_iteration as ready-made bf16 blocks (no stacked buffers): same bits as the
+    iteration that stacks and rounds the fp32 blocks itself."""
+    layers = inputs.cnn_iteration(scale=8, B=32, P=4)
+    out = []
+    for in_place in (False, True):
+        tasks, state = _build_iteration(layers, psd.BF16, [None] * len(layers))
+        if in_place:
+            switched = 0
+            for t in tasks:
+                if "delta" not in t:
+                    continue
+                plan = t["plan"]
+                one = psd.plan_layer(psd.LAYER_FC, plan.M, plan.N, plan.B, 1)
+                Ub, Vb = [], []
+                for p in range(plan.P):
+                    U, ldu, V, ldv = psd.alloc_factors(one, psd.BF16, DEV)
+                    psd.pack_factors(one, [t["delta"][p]], [t["act"][p]], psd.BF16, U, ldu, V, ldv)
+                    Ub.append(U)
+                    Vb.append(V)
+                assert psd.sfb_blocks_supported(plan, psd.BF16, ldu, ldv)
+                t.update(U=None, V=None, delta=Ub, act=Vb, ldu=ldu, ldv=ldv)
+                switched += 1
+            assert switched == 3
+        psd.Iteration(tasks).run(inputs.LR, inputs.MU, psd.RULE_ALG3)
+        torch.cuda.synchronize()
+        out.append([(W.cpu().numpy(), Mom.cpu().numpy()) for W, Mom in state])
+    for (w0, m0), (w1, m1) in zip(*out):
+        assert np.array_equal(w0, w1) and np.array_equal(m0, m1)
+
+
 def test_sfb_equals_ps_route_on_the_same_gradients():
     # Section 4.3.1: factors reconstruct the gradient exactly, so both routes agree
     d = inputs.fc_layer_integer(M=300, N=200, B=4, P=3, seed=31)
