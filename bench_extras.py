@@ -113,6 +113,28 @@ def fc_config(psd, inputs, torch, dev, cfg_id, dtype_name=None, working_set_mb=6
     t_sfb = _time_ms(torch, sfb, n_sets)
     t_both = _time_ms(torch, both, n_sets)
     t_bias = _time_ms(torch, bias, n_sets)
+    # the same reconstruction from the per-worker blocks read in place (no stacked copy): fp32 blocks as they are,
+    # bf16 blocks as senders that round before sending would deliver them (made here, outside the timing)
+    t_blocks = None
+    if dtype == psd.F32 and psd.sfb_blocks_supported(plan, dtype):
+        def blocks(i):
+            s = sets[i]
+            psd.sync_fc_sfb_blocks(plan, dtype, s["delta"], 0, s["act"], 0, s["W"], s["Mom"], inputs.LR, inputs.MU)
+        t_blocks = _time_ms(torch, blocks, n_sets)
+    elif dtype == psd.BF16 and psd.sfb_blocks_supported(plan, dtype, sets[0]["ldu"], sets[0]["ldv"]):
+        one = psd.plan_layer(psd.LAYER_FC, M, N, B, 1)
+        for s in sets:
+            s["Ub"], s["Vb"] = [], []
+            for p in range(P):
+                Ub, _, Vb, _ = psd.alloc_factors(one, dtype, dev)
+                psd.pack_factors(one, [s["delta"][p]], [s["act"][p]], dtype, Ub, s["ldu"], Vb, s["ldv"])
+                s["Ub"].append(Ub)
+                s["Vb"].append(Vb)
+
+        def blocks(i):
+            s = sets[i]
+            psd.sync_fc_sfb_blocks(plan, dtype, s["Ub"], s["ldu"], s["Vb"], s["ldv"], s["W"], s["Mom"], inputs.LR, inputs.MU)
+        t_blocks = _time_ms(torch, blocks, n_sets)
     flops = 2 * N * M * K
     bytes_sfb = 16 * N * M + K * (M + N) * es
     bytes_pack = K * (M + N) * (4 + es)
@@ -123,6 +145,7 @@ def fc_config(psd, inputs, torch, dev, cfg_id, dtype_name=None, working_set_mb=6
                 sfb_GBps=round(bytes_sfb / t_sfb / 1e6, 1), sfb_frac_hbm=round(bytes_sfb / t_sfb / 1e6 / PEAK_HBM_GBS, 4),
                 pack_ms=round(t_pack, 5), pack_GBps=round(bytes_pack / t_pack / 1e6, 1),
                 pack_plus_sfb_ms=round(t_both, 5), pack_plus_sfb_TFLOPs=round(flops / t_both / 1e9, 2),
+                sfb_blocks_in_place_ms=None if t_blocks is None else round(t_blocks, 5),
                 bias_ms=round(t_bias, 5), bias_GBps=round((K * N * es + 16 * N) / t_bias / 1e6, 1))
 
 
