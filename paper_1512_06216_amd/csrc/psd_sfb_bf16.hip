@@ -306,8 +306,8 @@ sfb_bf16_body(const uint16_t* __restrict__ U, int64_t ldu, const uint16_t* __res
                     const int64_t n = n0 + wn0 + 32 * bn + prow + 8 * jj;
                     d[jj] = *reinterpret_cast<const float4*>(patch + (prow + 8 * jj) * PLD + pcol);
                     if (n < N && m < M) {                  // m % 4 == 0 and M % 4 == 0: whole quad inside
-                        w[jj] = *reinterpret_cast<const float4*>(W + n * int64_t(M) + m);
-                        mo[jj] = *reinterpret_cast<const float4*>(Mom + n * int64_t(M) + m);
+                        w[jj] = load_stream4(W + n * int64_t(M) + m);
+                        mo[jj] = load_stream4(Mom + n * int64_t(M) + m);
                     }
                 }
 #pragma unroll
@@ -318,8 +318,8 @@ sfb_bf16_body(const uint16_t* __restrict__ U, int64_t ldu, const uint16_t* __res
                         upd(d[jj].y, w[jj].y, mo[jj].y, lr, mu, wd);
                         upd(d[jj].z, w[jj].z, mo[jj].z, lr, mu, wd);
                         upd(d[jj].w, w[jj].w, mo[jj].w, lr, mu, wd);
-                        *reinterpret_cast<float4*>(Mom + n * int64_t(M) + m) = mo[jj];
-                        *reinterpret_cast<float4*>(W + n * int64_t(M) + m) = w[jj];
+                        store_stream4(Mom + n * int64_t(M) + m, mo[jj]);
+                        store_stream4(W + n * int64_t(M) + m, w[jj]);
                     }
                 }
             }
@@ -342,10 +342,10 @@ sfb_bf16_body(const uint16_t* __restrict__ U, int64_t ldu, const uint16_t* __res
                         continue;
                     }
                     if (m < M) {
-                        float wv = wrow[m], mv = mrow[m];
+                        float wv = load_stream1(wrow + m), mv = load_stream1(mrow + m);
                         upd(acc[bn][bm][r], wv, mv, lr, mu, wd);
-                        mrow[m] = mv;
-                        wrow[m] = wv;
+                        store_stream1(mrow + m, mv);
+                        store_stream1(wrow + m, wv);
                     }
                 }
         }
