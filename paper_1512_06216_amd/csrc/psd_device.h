@@ -22,9 +22,9 @@ __device__ __forceinline__ void upd(float d, float& w, float& mo, float lr, floa
 // allocated in the XCD's 4 MB L2 on its way through and pushes out the factor panels that the workgroups
 // still in their MFMA loop are sharing there: measured on the bf16 reconstruction, the hint on both the
 // loads and the stores takes fc6 from 220 to 198 us and the 4096 -> 1000 layer from 38 to 31 us (either one
-// alone: no gain; the scope bits sc0 / sc1 on top of it: slower).
+// alone: no gain; the scope bits sc0 / sc1 on top of it: slower).  Only for accesses that cover whole
+// cache lines: streamed stores to parts of a line are expensive.
 typedef float f32x4_nt __attribute__((ext_vector_type(4)));
-typedef float f32x2_nt __attribute__((ext_vector_type(2)));
 __device__ __forceinline__ float4 load_stream4(const float* p)
 {
     const f32x4_nt v = __builtin_nontemporal_load(reinterpret_cast<const f32x4_nt*>(p));
@@ -35,18 +35,6 @@ __device__ __forceinline__ void store_stream4(float* p, float4 x)
     const f32x4_nt v = {x.x, x.y, x.z, x.w};
     __builtin_nontemporal_store(v, reinterpret_cast<f32x4_nt*>(p));
 }
-__device__ __forceinline__ float2 load_stream2(const float* p)
-{
-    const f32x2_nt v = __builtin_nontemporal_load(reinterpret_cast<const f32x2_nt*>(p));
-    return make_float2(v.x, v.y);
-}
-__device__ __forceinline__ void store_stream2(float* p, float2 x)
-{
-    const f32x2_nt v = {x.x, x.y};
-    __builtin_nontemporal_store(v, reinterpret_cast<f32x2_nt*>(p));
-}
-__device__ __forceinline__ float load_stream1(const float* p) { return __builtin_nontemporal_load(p); }
-__device__ __forceinline__ void store_stream1(float* p, float x) { __builtin_nontemporal_store(x, p); }
 
 // global -> LDS without registers, 16 bytes per lane: lane i's chunk lands at
 // lds_addr_uniform + 16*i.  A lane whose offset is at or past the descriptor's size writes zeros.

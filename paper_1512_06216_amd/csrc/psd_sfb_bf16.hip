@@ -79,7 +79,7 @@ __device__ __forceinline__ const uint16_t* uniform_ptr(const uint16_t* p)
     return reinterpret_cast<const uint16_t*>((static_cast<uint64_t>(hi) << 32) | lo);
 }
 
-template <class C, bool PART, bool BLK>
+template <class C, bool PART, bool BLK, bool STREAM>
 __device__ __forceinline__ void
 sfb_bf16_body(const uint16_t* __restrict__ U, int64_t ldu, const uint16_t* __restrict__ V, int64_t ldv,
               float* __restrict__ W, float* __restrict__ Mom, int N, int M, int K, float lr, float mu, float wd,
@@ -280,6 +280,10 @@ sfb_bf16_body(const uint16_t* __restrict__ U, int64_t ldu, const uint16_t* __res
         // held, read back with 8 lanes per row, then 8 rows x 128 bytes per global access.
         float* patch = reinterpret_cast<float*>(lds) + wave * (32 * PLD);
         const int prow = lane >> 3, pcol = 4 * (lane & 7);
+        // STREAM: W / Mom with the streaming hint.  The host asks for it when their rows start on cache-line
+        // boundaries (every 128-byte access is then a whole line); with rows that start mid-line (M = 3000)
+        // the hint makes the partial-line stores expensive (measured 3000 -> 21841: 468 -> 534 us).
+        constexpr bool stream = STREAM;
 #pragma unroll
         for (int bn = 0; bn < C::BN; ++bn) {
 #pragma unroll
@@ -306,8 +310,10 @@ sfb_bf16_body(const uint16_t* __restrict__ U, int64_t ldu, const uint16_t* __res
                     const int64_t n = n0 + wn0 + 32 * bn + prow + 8 * jj;
                     d[jj] = *reinterpret_cast<const float4*>(patch + (prow + 8 * jj) * PLD + pcol);
                     if (n < N && m < M) {                  // m % 4 == 0 and M % 4 == 0: whole quad inside
-                        w[jj] = load_stream4(W + n * int64_t(M) + m);
-                        mo[jj] = load_stream4(Mom + n * int64_t(M) + m);
+                        const float* wp = W + n * int64_t(M) + m;
+                        const float* mp = Mom + n * int64_t(M) + m;
+                        w[jj] = stream ? load_stream4(wp) : *reinterpret_cast<const float4*>(wp);
+                        mo[jj] = stream ? load_stream4(mp) : *reinterpret_cast<const float4*>(mp);
                     }
                 }
 #pragma unroll
@@ -318,8 +324,13 @@ sfb_bf16_body(const uint16_t* __restrict__ U, int64_t ldu, const uint16_t* __res
                         upd(d[jj].y, w[jj].y, mo[jj].y, lr, mu, wd);
                         upd(d[jj].z, w[jj].z, mo[jj].z, lr, mu, wd);
                         upd(d[jj].w, w[jj].w, mo[jj].w, lr, mu, wd);
-                        store_stream4(Mom + n * int64_t(M) + m, mo[jj]);
-                        store_stream4(W + n * int64_t(M) + m, w[jj]);
+                        if (stream) {
+                            store_stream4(Mom + n * int64_t(M) + m, mo[jj]);
+                            store_stream4(W + n * int64_t(M) + m, w[jj]);
+                        } else {
+                            *reinterpret_cast<float4*>(Mom + n * int64_t(M) + m) = mo[jj];
+                            *reinterpret_cast<float4*>(W + n * int64_t(M) + m) = w[jj];
+                        }
                     }
                 }
             }
@@ -342,35 +353,35 @@ sfb_bf16_body(const uint16_t* __restrict__ U, int64_t ldu, const uint16_t* __res
                         continue;
                     }
                     if (m < M) {
-                        float wv = load_stream1(wrow + m), mv = load_stream1(mrow + m);
+                        float wv = wrow[m], mv = mrow[m];
                         upd(acc[bn][bm][r], wv, mv, lr, mu, wd);
-                        store_stream1(mrow + m, mv);
-                        store_stream1(wrow + m, wv);
+                        mrow[m] = mv;
+                        wrow[m] = wv;
                     }
                 }
         }
     }
 }
 
-template <class C, bool PART>
+template <class C, bool PART, bool STREAM>
 __global__ void __launch_bounds__(C::THREADS, C::OCC)
 sfb_bf16_kernel(const uint16_t* __restrict__ U, int64_t ldu, const uint16_t* __restrict__ V, int64_t ldv,
                 float* __restrict__ W, float* __restrict__ Mom, int N, int M, int K, float lr, float mu, float wd,
                 int tiles_n, int tiles_m, uint32_t u_bytes, uint32_t v_bytes, float* __restrict__ part,
                 int64_t part_stride, int stages_per_split, int skew_blocks, int skew_ticks)
 {
-    sfb_bf16_body<C, PART, false>(U, ldu, V, ldv, W, Mom, N, M, K, lr, mu, wd, tiles_n, tiles_m, u_bytes, v_bytes, part,
+    sfb_bf16_body<C, PART, false, STREAM>(U, ldu, V, ldv, W, Mom, N, M, K, lr, mu, wd, tiles_n, tiles_m, u_bytes, v_bytes, part,
                                   part_stride, stages_per_split, skew_blocks, skew_ticks, nullptr, 0, 0);
 }
 
 // the P per-worker blocks read in place (u_bytes, v_bytes: the size of ONE block)
-template <class C>
+template <class C, bool STREAM>
 __global__ void __launch_bounds__(C::THREADS, C::OCC)
 sfb_bf16_blocks_kernel(BlockPtrs blocks, int n_blocks, int stages_per_block, int64_t ldu, int64_t ldv,
                        float* __restrict__ W, float* __restrict__ Mom, int N, int M, int K, float lr, float mu, float wd,
                        int tiles_n, int tiles_m, uint32_t u_bytes, uint32_t v_bytes)
 {
-    sfb_bf16_body<C, false, true>(nullptr, ldu, nullptr, ldv, W, Mom, N, M, K, lr, mu, wd, tiles_n, tiles_m, u_bytes,
+    sfb_bf16_body<C, false, true, STREAM>(nullptr, ldu, nullptr, ldv, W, Mom, N, M, K, lr, mu, wd, tiles_n, tiles_m, u_bytes,
                                   v_bytes, nullptr, 0, 0, 0, 0, &blocks, n_blocks, stages_per_block);
 }
 
@@ -383,13 +394,16 @@ psd_status launch_cfg_blocks(const BlockPtrs& blocks, int64_t P, int64_t B, int6
     if (tiles < 1 || tiles > 0x3fffffff) return PSD_E_INVALID;
     const int64_t u_bytes = B * ldu * 2, v_bytes = B * ldv * 2;          // one block
     if (u_bytes >= (int64_t(1) << 32) || v_bytes >= (int64_t(1) << 32)) return PSD_E_UNSUPPORTED;
+    auto kern = M % 32 == 0 ? sfb_bf16_blocks_kernel<C, true> : sfb_bf16_blocks_kernel<C, false>;
     static std::atomic<bool> attr_done{false};
     if (!attr_done.load(std::memory_order_acquire)) {
-        PSD_HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(sfb_bf16_blocks_kernel<C>),
+        PSD_HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(sfb_bf16_blocks_kernel<C, true>),
+                                        hipFuncAttributeMaxDynamicSharedMemorySize, int(C::LDS_BYTES)));
+        PSD_HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(sfb_bf16_blocks_kernel<C, false>),
                                         hipFuncAttributeMaxDynamicSharedMemorySize, int(C::LDS_BYTES)));
         attr_done.store(true, std::memory_order_release);
     }
-    hipLaunchKernelGGL(sfb_bf16_blocks_kernel<C>, dim3(static_cast<uint32_t>(tiles)), dim3(C::THREADS), C::LDS_BYTES, st,
+    hipLaunchKernelGGL(kern, dim3(static_cast<uint32_t>(tiles)), dim3(C::THREADS), C::LDS_BYTES, st,
                        blocks, static_cast<int>(P), static_cast<int>(B / KT), ldu, ldv, W, Mom, static_cast<int>(N),
                        static_cast<int>(M), static_cast<int>(P * B), lr, mu, wd, static_cast<int>(tiles_n),
                        static_cast<int>(tiles_m), static_cast<uint32_t>(u_bytes), static_cast<uint32_t>(v_bytes));
@@ -409,14 +423,18 @@ psd_status launch_cfg(const uint16_t* U, int64_t ldu, const uint16_t* V, int64_t
     const int64_t u_bytes = K * ldu * 2, v_bytes = K * ldv * 2;
     const int64_t reach = (int64_t(1) << 32) - (C::NSTAGE + 2) * KT * (ldu > ldv ? ldu : ldv) * 2 - 4096;
     if (u_bytes > reach || v_bytes > reach) return PSD_E_UNSUPPORTED;
-    auto kern = splits > 1 ? sfb_bf16_kernel<C, true> : sfb_bf16_kernel<C, false>;
+    // W / Mom are streamed when their rows start on cache-line boundaries (see the epilogue)
+    auto kern = splits > 1 ? sfb_bf16_kernel<C, true, false>
+                           : (M % 32 == 0 ? sfb_bf16_kernel<C, false, true> : sfb_bf16_kernel<C, false, false>);
     // raise the dynamic LDS limit once per process (idempotent, so a race between two first
     // callers is harmless; the flag only saves the call on later launches)
     static std::atomic<bool> attr_done{false};
     if (!attr_done.load(std::memory_order_acquire)) {
-        PSD_HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(sfb_bf16_kernel<C, true>),
+        PSD_HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(sfb_bf16_kernel<C, true, false>),
                                         hipFuncAttributeMaxDynamicSharedMemorySize, int(C::LDS_BYTES)));
-        PSD_HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(sfb_bf16_kernel<C, false>),
+        PSD_HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(sfb_bf16_kernel<C, false, true>),
+                                        hipFuncAttributeMaxDynamicSharedMemorySize, int(C::LDS_BYTES)));
+        PSD_HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(sfb_bf16_kernel<C, false, false>),
                                         hipFuncAttributeMaxDynamicSharedMemorySize, int(C::LDS_BYTES)));
         attr_done.store(true, std::memory_order_release);
     }

@@ -212,23 +212,23 @@ sfb_f32_body(const float* __restrict__ U, int64_t ldu, const float* __restrict__
             float* wp = W + n * int64_t(M) + mcol;
             float* mp = Mom + n * int64_t(M) + mcol;
             if (pair_ok && mcol + 1 < M) {
-                float2 w = load_stream2(wp), mo = load_stream2(mp);
+                float2 w = *reinterpret_cast<float2*>(wp), mo = *reinterpret_cast<float2*>(mp);
                 upd(d0, w.x, mo.x, lr, mu, wd);
                 upd(d1, w.y, mo.y, lr, mu, wd);
-                store_stream2(mp, mo);
-                store_stream2(wp, w);
+                *reinterpret_cast<float2*>(mp) = mo;
+                *reinterpret_cast<float2*>(wp) = w;
             } else {
                 if (mcol < M) {
-                    float w = load_stream1(wp), mo = load_stream1(mp);
+                    float w = wp[0], mo = mp[0];
                     upd(d0, w, mo, lr, mu, wd);
-                    store_stream1(mp, mo);
-                    store_stream1(wp, w);
+                    mp[0] = mo;
+                    wp[0] = w;
                 }
                 if (mcol + 1 < M) {
-                    float w = load_stream1(wp + 1), mo = load_stream1(mp + 1);
+                    float w = wp[1], mo = mp[1];
                     upd(d1, w, mo, lr, mu, wd);
-                    store_stream1(mp + 1, mo);
-                    store_stream1(wp + 1, w);
+                    mp[1] = mo;
+                    wp[1] = w;
                 }
             }
         }
