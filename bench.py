@@ -40,7 +40,7 @@ PREWARM_MS = 150.0      # untimed work before the W warm-up steps: the clocks of
 # HBM bytes per launch of the dominant kernel measured with rocprofv3 --pmc (FETCH_SIZE and
 # WRITE_SIZE runs, scaled by a copy kernel of known size); filled in from the committed
 # profile summaries, None where not measured.
-MEASURED_TRAFFIC_BYTES = {"bf16": 931_300_000, "f32": None}   # fc6 launch; profiles/bench_config5_bf16_hbm_traffic.txt
+MEASURED_TRAFFIC_BYTES = {"bf16": 938_400_000, "f32": None}   # fc6 launch; profiles/bench_config5_bf16_hbm_traffic.txt
 
 
 class HipEvents:

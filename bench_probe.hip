@@ -22,7 +22,8 @@ typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 // ---------------------------------------------------------------------------------------------------
 struct Ptrs { const float* g[8]; };
 
-template <int P>
+// NT: W and Mom are read and written with the streaming (non-temporal) hint as well, like the P read-only arrays
+template <int P, bool NT>
 __global__ void __launch_bounds__(256) stream_kernel(Ptrs in, float* __restrict__ W, float* __restrict__ Mom, size_t n4)
 {
     const size_t base = size_t(blockIdx.x) * 512 + threadIdx.x;
@@ -33,15 +34,27 @@ __global__ void __launch_bounds__(256) stream_kernel(Ptrs in, float* __restrict_
         f32x4 acc = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
         for (int p = 0; p < P; ++p) acc += __builtin_nontemporal_load(reinterpret_cast<const f32x4*>(in.g[p]) + i);
-        f32x4 w = reinterpret_cast<f32x4*>(W)[i], m = reinterpret_cast<f32x4*>(Mom)[i];
+        f32x4 w, m;
+        if constexpr (NT) {
+            w = __builtin_nontemporal_load(reinterpret_cast<f32x4*>(W) + i);
+            m = __builtin_nontemporal_load(reinterpret_cast<f32x4*>(Mom) + i);
+        } else {
+            w = reinterpret_cast<f32x4*>(W)[i];
+            m = reinterpret_cast<f32x4*>(Mom)[i];
+        }
         m = 0.9f * m + 0.01f * acc;
         w = w - m;
-        reinterpret_cast<f32x4*>(Mom)[i] = m;
-        reinterpret_cast<f32x4*>(W)[i] = w;
+        if constexpr (NT) {
+            __builtin_nontemporal_store(m, reinterpret_cast<f32x4*>(Mom) + i);
+            __builtin_nontemporal_store(w, reinterpret_cast<f32x4*>(W) + i);
+        } else {
+            reinterpret_cast<f32x4*>(Mom)[i] = m;
+            reinterpret_cast<f32x4*>(W)[i] = w;
+        }
     }
 }
 
-template <int P>
+template <int P, bool NT>
 static void run_stream(size_t n, hipEvent_t e0, hipEvent_t e1)
 {
     const int sets = 2;
@@ -53,18 +66,18 @@ static void run_stream(size_t n, hipEvent_t e0, hipEvent_t e1)
     }
     const size_t n4 = n / 4;
     const unsigned grid = static_cast<unsigned>((n4 + 511) / 512);
-    for (int i = 0; i < 60; ++i) stream_kernel<P><<<grid, 256>>>(in[i % sets], W[i % sets], Mom[i % sets], n4);
+    for (int i = 0; i < 60; ++i) stream_kernel<P, NT><<<grid, 256>>>(in[i % sets], W[i % sets], Mom[i % sets], n4);
     CK(hipDeviceSynchronize());
     float best = 1e30f, sum = 0;
     for (int rep = 0; rep < 5; ++rep) {
         CK(hipEventRecord(e0));
-        for (int i = 0; i < 20; ++i) stream_kernel<P><<<grid, 256>>>(in[i % sets], W[i % sets], Mom[i % sets], n4);
+        for (int i = 0; i < 20; ++i) stream_kernel<P, NT><<<grid, 256>>>(in[i % sets], W[i % sets], Mom[i % sets], n4);
         CK(hipEventRecord(e1)); CK(hipEventSynchronize(e1));
         float ms; CK(hipEventElapsedTime(&ms, e0, e1)); ms /= 20; sum += ms; if (ms < best) best = ms;
     }
     const double bytes = double(n) * (4.0 * P + 16.0);
-    printf("  P = %d reads + W/Mom read-modify-write, %10zu keys: mean %8.1f us = %6.0f GB/s (%.1f %% of 8 TB/s), best %8.1f us\n",
-           P, n, sum / 5 * 1e3, bytes / (sum / 5) / 1e6, bytes / (sum / 5) / 1e6 / 80.0, best * 1e3);
+    printf("  P = %d reads + W/Mom read-modify-write (%s), %10zu keys: mean %8.1f us = %6.0f GB/s (%.1f %% of 8 TB/s), best %8.1f us\n",
+           P, NT ? "W/Mom streamed" : "W/Mom cached  ", n, sum / 5 * 1e3, bytes / (sum / 5) / 1e6, bytes / (sum / 5) / 1e6 / 80.0, best * 1e3);
     for (int s = 0; s < sets; ++s) { for (int p = 0; p < P; ++p) CK(hipFree(const_cast<float*>(in[s].g[p]))); CK(hipFree(W[s])); CK(hipFree(Mom[s])); }
 }
 
@@ -241,10 +254,15 @@ int main(int argc, char** argv)
     const char* what = argc > 1 ? argv[1] : "stream";
     if (!strcmp(what, "stream")) {
         printf("bare streams (two rotating buffer sets, 20 launches per timing, mean of 5):\n");
-        for (size_t n : {size_t(2332704), size_t(16777216), size_t(37748736), size_t(89460736)}) run_stream<8>(n, e0, e1);
-        run_stream<0>(37748736, e0, e1);
-        run_stream<1>(37748736, e0, e1);
-        run_stream<4>(37748736, e0, e1);
+        for (size_t n : {size_t(2332704), size_t(16777216), size_t(37748736), size_t(89460736)}) {
+            run_stream<8, false>(n, e0, e1);
+            run_stream<8, true>(n, e0, e1);
+        }
+        run_stream<0, false>(37748736, e0, e1);
+        run_stream<0, true>(37748736, e0, e1);
+        run_stream<1, false>(37748736, e0, e1);
+        run_stream<4, false>(37748736, e0, e1);
+        run_stream<4, true>(37748736, e0, e1);
     } else if (!strcmp(what, "coresident")) {
         printf("one launch, two kinds of workgroups (each 256 lanes, at most two per CU); times per workgroup from the 100 MHz clock:\n");
         run_coresident(e0, e1);
