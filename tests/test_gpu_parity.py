@@ -569,6 +569,38 @@ def test_sfb_blocks_in_place_bit_exact_and_identical_to_the_stacked_path(M, N, B
     assert np.array_equal(Mom.cpu().numpy(), Ms) and np.array_equal(W.cpu().numpy(), Ws)
 
 
+@pytest.mark.parametrize("seed", range(6))
+def test_sfb_blocks_in_place_random_shapes_identical_to_the_stacked_path(seed):
+    """Random layer shapes, worker counts and block paddings, both factor dtypes: the blocks read in place give
+    the very bits of the stacked path (which the other tests tie to the oracle)."""
+    rng = np.random.default_rng(4200 + seed)
+    for dtype, stage, q in ((psd.F32, 16, 4), (psd.BF16, 32, 8)):
+        M, N = int(rng.integers(1, 700)), int(rng.integers(1, 500))
+        P, B = int(rng.integers(1, 10)), stage * int(rng.integers(1, 4))
+        # block rows: the narrowest the entry point accepts, or padded further
+        ldu = (N + q - 1) // q * q + q * int(rng.integers(0, 3))
+        ldv = (M + q - 1) // q * q + q * int(rng.integers(0, 3))
+        td = torch.float32 if dtype == psd.F32 else torch.bfloat16
+        plan = psd.plan_layer(psd.LAYER_FC, M, N, B, P)
+        assert psd.sfb_blocks_supported(plan, dtype, ldu, ldv), (M, N, B, P, ldu, ldv)
+        d = inputs.fc_layer(M=M, N=N, B=B, P=P, seed=900 + seed, mom_std=1e-4)
+        Ub, Vb = [], []
+        for p in range(P):
+            u = torch.zeros(B, ldu, dtype=td, device=DEV)
+            v = torch.zeros(B, ldv, dtype=td, device=DEV)
+            u[:, :N] = dev(d["delta"][p]).to(td)         # torch rounds to nearest even, as the pack kernel does
+            v[:, :M] = dev(d["act"][p]).to(td)
+            Ub.append(u)
+            Vb.append(v)
+        U, V = torch.cat(Ub).contiguous(), torch.cat(Vb).contiguous()      # the stacked matrices, same leading dimensions
+        Ws, Ms = dev(d["W"]), dev(d["Mom"])
+        psd.sync_fc_sfb(plan, dtype, U, ldu, V, ldv, Ws, Ms, inputs.LR, inputs.MU, wd=1e-3)
+        Wb, Mb = dev(d["W"]), dev(d["Mom"])
+        psd.sync_fc_sfb_blocks(plan, dtype, Ub, ldu, Vb, ldv, Wb, Mb, inputs.LR, inputs.MU, wd=1e-3)
+        torch.cuda.synchronize()
+        assert torch.equal(Ws, Wb) and torch.equal(Ms, Mb), (M, N, B, P, ldu, ldv, dtype)
+
+
 def test_sfb_blocks_in_place_at_the_classifier_size():
     """Config 2 (4096 -> 1000, K = 2048, fp32) without the stacking pass: whole matrix against the oracle."""
     d = inputs.fc_config(2)
