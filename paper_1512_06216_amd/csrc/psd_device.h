@@ -57,6 +57,16 @@ __device__ __forceinline__ void wait_vmcnt()
     asm volatile("s_waitcnt vmcnt(%0)" : : "n"(N) : "memory");
 }
 
+// A pointer every lane holds alike, moved to scalar registers (buffer descriptors live there).
+template <class T>
+__device__ __forceinline__ const T* uniform_ptr(const T* p)
+{
+    const uint64_t a = reinterpret_cast<uint64_t>(p);
+    const uint32_t lo = __builtin_amdgcn_readfirstlane(static_cast<uint32_t>(a));
+    const uint32_t hi = __builtin_amdgcn_readfirstlane(static_cast<uint32_t>(a >> 32));
+    return reinterpret_cast<const T*>((static_cast<uint64_t>(hi) << 32) | lo);
+}
+
 // Raw buffer descriptor over `bytes` bytes at X (stride 0: byte-granular range check).
 __device__ __forceinline__ i32x4 raw_rsrc(const void* X, uint32_t bytes)
 {

@@ -70,15 +70,6 @@ __device__ __forceinline__ bf16x4 read_tr(uint32_t lds_addr)
 // block (and aimed at nothing past the last one, which reads as zeros like the K tail does).
 struct BlockPtrs { const uint16_t* u[PSD_MAX_WORKERS]; const uint16_t* v[PSD_MAX_WORKERS]; };
 
-// a pointer every lane holds alike, moved to scalar registers (buffer descriptors live there)
-__device__ __forceinline__ const uint16_t* uniform_ptr(const uint16_t* p)
-{
-    const uint64_t a = reinterpret_cast<uint64_t>(p);
-    const uint32_t lo = __builtin_amdgcn_readfirstlane(static_cast<uint32_t>(a));
-    const uint32_t hi = __builtin_amdgcn_readfirstlane(static_cast<uint32_t>(a >> 32));
-    return reinterpret_cast<const uint16_t*>((static_cast<uint64_t>(hi) << 32) | lo);
-}
-
 template <class C, bool PART, bool BLK, bool STREAM>
 __device__ __forceinline__ void
 sfb_bf16_body(const uint16_t* __restrict__ U, int64_t ldu, const uint16_t* __restrict__ V, int64_t ldv,

@@ -44,15 +44,6 @@ constexpr int NSTAGE = 4;           // ring depth
 // next block (and aimed at nothing past the last one, which reads as zeros like the K tail does).
 struct BlockPtrs { const float* u[PSD_MAX_WORKERS]; const float* v[PSD_MAX_WORKERS]; };
 
-// a pointer every lane holds alike, moved to scalar registers (buffer descriptors live there)
-__device__ __forceinline__ const float* uniform_ptr(const float* p)
-{
-    const uint64_t a = reinterpret_cast<uint64_t>(p);
-    const uint32_t lo = __builtin_amdgcn_readfirstlane(static_cast<uint32_t>(a));
-    const uint32_t hi = __builtin_amdgcn_readfirstlane(static_cast<uint32_t>(a >> 32));
-    return reinterpret_cast<const float*>((static_cast<uint64_t>(hi) << 32) | lo);
-}
-
 template <int BN, bool PART, bool BLK>
 __device__ __forceinline__ void
 sfb_f32_body(const float* __restrict__ U, int64_t ldu, const float* __restrict__ V, int64_t ldv,
