@@ -19,11 +19,13 @@ __device__ __forceinline__ void upd(float d, float& w, float& mo, float lr, floa
 
 // Streaming ("non-temporal") accesses for data that is touched exactly once per launch -- W and Mom in
 // every update, the gradient copies of the parameter-server sum.  Without the hint every W / Mom line is
-// allocated in the XCD's 4 MB L2 on its way through and pushes out the factor panels that the workgroups
-// still in their MFMA loop are sharing there: measured on the bf16 reconstruction, the hint on both the
-// loads and the stores takes fc6 from 220 to 198 us and the 4096 -> 1000 layer from 38 to 31 us (either one
-// alone: no gain; the scope bits sc0 / sc1 on top of it: slower).  Only for accesses that cover whole
-// cache lines: streamed stores to parts of a line are expensive.
+// allocated in the XCD's 4 MB L2 on its way through and the update leaves the L2 full of dirty lines; the
+// factor fetches of the workgroups that are in their MFMA loop then have those write-backs on their miss
+// path.  Measured on the bf16 reconstruction: the hint on both the loads and the stores takes fc6 from
+// 220 to 198 us and the 4096 -> 1000 layer from 38 to 31 us while the bytes that cross the L2 / fabric
+// boundary stay the same (636 against 630 MB) and the mean L1 -> L2 read latency falls from 477 to 404
+// cycles (either hint alone: no gain; the scope bits sc0 / sc1 on top: slower).  Only for accesses that
+// cover whole cache lines: streamed stores to parts of a line are expensive.
 typedef float f32x4_nt __attribute__((ext_vector_type(4)));
 __device__ __forceinline__ float4 load_stream4(const float* p)
 {
